@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the LagKV compression pass on one MI355X.
+
+A step is one whole pass of the hot path (score -> per-chunk top-k -> compaction,
+K, V and their original indices written) over one batch of synthetic KV that is
+already resident in HBM.  Default workload: the 128K-context headline
+configuration (Llama-3-8B-shaped bf16 cache, 32 layers x 8 KV heads x D=128, B=4,
+T=131072, S=16, L=512, r=0.25; 64 GiB scanned per pass).
+
+Prints ONE JSON line (see README for the fields).  `--workload decode`
+times the decode-time variant (config 5) instead.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(streams: int, T: int, T_out: int, D: int, esize: int, with_idx: bool = True) -> int:
+    """Each input element read once, each kept element written once (K and V), plus the
+    int32 source index of every output row."""
+    return streams * (2 * esize * D * (T + T_out) + (4 * T_out if with_idx else 0))
+
+
+def read_traffic(name: str):
+    """HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy kernel of known size); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline_compress(K, V, cfg, stream_ids, layers_x_heads: int):
+    """Times the oracle (as it stands) on a bounded sample of streams copied from the
+    device: single thread, then one thread per stream over the host cores."""
+    import numpy as np
+    import torch
+    from oracle import lagkv_oracle as O
+
+    host = []
+    for s in stream_ids:
+        b, h = divmod(s, cfg.H)
+        host.append((K[b, h].cpu(), V[b, h].cpu()))
+
+    def one(kv):
+        k, v = kv
+        return O.compress(k.double().numpy(), v.double().numpy(), cfg.S, cfg.L, cfg.r,
+                          raw=(k.view(torch.int16).numpy(), v.view(torch.int16).numpy()))[2].shape[0]
+
+    n1 = max(1, len(host) // 4)
+    t0 = time.perf_counter()
+    for kv in host[:n1]:
+        one(kv)
+    t_single = time.perf_counter() - t0
+    threads = max(1, min(16, os.cpu_count() or 1, len(host)))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, host))
+    t_multi = time.perf_counter() - t0
+    tok_single = n1 * cfg.T / t_single / layers_x_heads
+    tok_multi = len(host) * cfg.T / t_multi / layers_x_heads
+    best_multi = tok_multi >= tok_single
+    return {
+        "value": tok_multi if best_multi else tok_single,
+        "unit": "tokens/s",
+        "cores": threads if best_multi else 1,
+        "kind": "oracle",
+        "sample": f"{len(host)} of {cfg.streams} whole (layer,batch,head) streams of the same cache, "
+                  f"copied from the device; fp64 NumPy oracle; extrapolated to all streams; "
+                  f"single thread on {n1} streams: {tok_single:.1f} tokens/s, "
+                  f"{threads} threads on {len(host)} streams: {tok_multi:.1f} tokens/s",
+    }
+
+
+def bench_compress(args):
+    import torch
+    from paper_2504_04704_amd import lagkv, synth
+
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    lagkv.load()
+    if args.waves:
+        lagkv.tune(lagkv.TUNE_WAVES, args.waves)
+    if args.segments:
+        lagkv.tune(lagkv.TUNE_SEGMENTS, args.segments)
+    t0 = time.perf_counter()
+    K, V = synth.make_kv(cfg, device=dev)
+    torch.cuda.synchronize()
+    print(f"[bench] generated {cfg.name}: {2 * K.numel() * K.element_size() / 2**30:.1f} GiB in "
+          f"{time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r)
+    pl = lagkv.plan(p, cfg.T)
+    Bf, H, T, D = K.shape
+    Ko = torch.empty((Bf, H, pl.T_out, D), dtype=K.dtype, device=dev)
+    Vo = torch.empty_like(Ko)
+    idx = torch.empty((Bf, H, pl.T_out), dtype=torch.int32, device=dev)
+
+    def step():
+        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, out=(Ko, Vo), idx_out=idx)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    tokens = cfg.B * cfg.T                      # one token = one (batch, position) over all layers and heads
+    alg = algorithmic_bytes(cfg.streams, cfg.T, pl.T_out, cfg.D, K.element_size())
+    achieved = alg / (kern_avg_ms * 1e-3) / 1e9
+    traffic = read_traffic(f"fused_pass_{cfg.name}_traffic.txt")
+    res = {
+        "metric": "kv_tokens_compressed_per_sec_128k_ctx" if cfg.T == 131072 else "kv_tokens_compressed_per_sec",
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": cfg.layers, "B": cfg.B, "H_kv": cfg.H, "D": cfg.D,
+                   "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype,
+                   "T_out": int(pl.T_out), "streams": cfg.streams,
+                   "head_tokens_per_s": cfg.streams * cfg.T / (ms_per_step * 1e-3)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "fused_pass_kernel", "kernel_ms_avg": kern_avg_ms,
+                     "kernel_ms_min": min(kern_ms), "algorithmic_bytes": alg},
+    }
+    if not args.no_cpu:
+        ids = synth.stream_sample(cfg.streams, args.cpu_streams)
+        res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H)
+    return res
+
+
+def bench_decode(args):
+    """Config 5: start from a compressed T=32768 cache at batch B, append L tokens per
+    sequence per call; reports per-call latency and sustained tokens/s."""
+    import torch
+    from paper_2504_04704_amd import lagkv, synth
+
+    cfg = synth.CONFIGS["cfg5_decode_b32"]
+    if args.decode_batch:
+        cfg = cfg.scaled(B=args.decode_batch)
+    dev = "cuda:0"
+    lagkv.load()
+    rounds = args.steps + args.warmup
+    pl = lagkv.plan(lagkv.make_params(cfg.layers * cfg.B, cfg.H, cfg.D, cfg.S, cfg.L, cfg.r), cfg.T)
+    cap = pl.T_out + rounds * pl.k + cfg.L
+    cache = lagkv.Cache(cfg.layers * cfg.B, cfg.H, cfg.D, cap, cfg.S, cfg.L, cfg.r, track_positions=True)
+    # build the compressed starting cache layer by layer (the uncompressed one is 128 GiB at B=32)
+    one = cfg.scaled(layers=1)
+    Kl = torch.empty((cfg.B, cfg.H, cfg.T, cfg.D), dtype=torch.bfloat16, device=dev)
+    Vl = torch.empty_like(Kl)
+    for l in range(cfg.layers):
+        synth.fill_layer(cfg, synth.MASTER_SEED, l, Kl, Vl)
+        comp = lagkv.compress(Kl, Vl, cfg.S, cfg.L, cfg.r)
+        sl = slice(l * cfg.B, (l + 1) * cfg.B)
+        cache.K[sl, :, :pl.T_out].copy_(comp.K)
+        cache.V[sl, :, :pl.T_out].copy_(comp.V)
+        cache.pos[sl, :, :pl.T_out].copy_(comp.idx)
+    del Kl, Vl, comp, one
+    cache.c.n_static, cache.c.n_tail, cache.c.n_seen = cfg.S + pl.k * pl.n_scored, pl.T_out - (cfg.S + pl.k * pl.n_scored), cfg.T
+    torch.cuda.synchronize()
+    new = [synth.make_new_tokens(cfg, cfg.L, i % 4, device=dev) for i in range(4)]
+    lat = []
+    for i in range(rounds):
+        Kn, Vn = new[i % 4]
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        s.record()
+        cache.append_and_compress(Kn, Vn)
+        e.record()
+        torch.cuda.synchronize()
+        if i >= args.warmup:
+            lat.append(((time.perf_counter() - t0) * 1e3, s.elapsed_time(e)))
+    wall = sorted(x[0] for x in lat)
+    dev_ms = sorted(x[1] for x in lat)
+    ms = sum(wall) / len(wall)
+    tokens = cfg.B * cfg.L
+    # per stream and call: read chunk + reference + remainder (2L + m... ) and write kept + slid tail
+    rowb = cfg.D * 2 * 2
+    m = (cfg.T - cfg.S) % cfg.L
+    alg = cfg.streams * ((cfg.L + 2 * cfg.L + m) + (cfg.L + pl.k + cfg.L + m)) * rowb
+    return {
+        "metric": "decode_append_and_compress_tokens_per_sec", "value": tokens / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "streams": cfg.streams, "T0": cfg.T, "L": cfg.L,
+                   "r": cfg.r, "n_new": cfg.L, "latency_ms_p50": wall[len(wall) // 2],
+                   "latency_ms_p99": wall[min(len(wall) - 1, int(len(wall) * 0.99))],
+                   "device_ms_p50": dev_ms[len(dev_ms) // 2], "final_length": cache.length},
+        "roofline": {"bound": "hbm", "achieved": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "fused_append_kernel", "algorithmic_bytes": alg},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", choices=["compress", "decode"], default="compress")
+    ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--cpu-streams", type=int, default=32)
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--decode-batch", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (every stream is independent; no "
+              "collective exists on this path). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    res = bench_compress(args) if args.workload == "compress" else bench_decode(args)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,186 @@
+/*
+ * lagkv.h - C ABI of the LagKV KV-cache compression pass for AMD MI355X (gfx950).
+ *
+ * The pass is the one defined in "LagKV: Lag-Relative Information of the KV
+ * Cache Tells Which Tokens Are Important" (arXiv 2504.04704), Methodology,
+ * subsection "LagKV": the cache of every KV head is split into S attention
+ * sink rows, chunks of L rows ("lag size") and a trailing sliding window; a
+ * chunk is scored against the NEXT chunk (Eq. 7-11), the k = floor(r*L) best
+ * rows of each chunk are kept and everything is compacted into a dense cache
+ * whose length is given by Eq. 12.
+ *
+ * General conventions
+ *   - Every K/V/score/index pointer is a DEVICE pointer owned by the caller.
+ *     The parameter, plan and cache structs are HOST memory.
+ *   - Tensors are [B, H, T, D]; the channel axis D is contiguous, the other
+ *     strides are given in ELEMENTS in lagkv_params (0 = dense default).
+ *     Layers may be folded into B: streams never interact.
+ *   - All (b, h) streams have the same length, because every head keeps
+ *     exactly k rows per chunk.
+ *   - Calls validate on the host, enqueue on the given HIP stream
+ *     (hipStream_t passed as void*, NULL = default stream) and return without
+ *     synchronising.  Output sizes are pure functions of (T, S, L, k), see
+ *     lagkv_plan.  Nothing is enqueued when validation fails.
+ *   - The library allocates no device memory and keeps no per-call state.
+ *   - Return value: a lagkv_status.  Inputs must be finite; NaN/Inf give
+ *     unspecified scores (never out-of-bounds accesses).
+ *   - Arithmetic: inputs as stored (fp32 or bf16), all scoring math in fp32,
+ *     scores fp32, kept rows copied bit for bit.
+ */
+#ifndef LAGKV_H
+#define LAGKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LAGKV_OK = 0,
+  LAGKV_EINVAL = 1,     /* null pointer, r outside (0,1], k = floor(r*L) < 1, S < 0, L < 1 ... */
+  LAGKV_ESHAPE = 2,     /* B/H/D/T/strides inconsistent or beyond the supported limits          */
+  LAGKV_EDTYPE = 3,     /* unknown dtype or variant                                              */
+  LAGKV_ECAPACITY = 4,  /* lagkv_cache too small for the rows to be appended                     */
+  LAGKV_EWORKSPACE = 5, /* workspace pointer missing or shorter than lagkv_workspace_bytes()     */
+  LAGKV_EHIP = 6        /* a HIP runtime call or kernel launch failed                            */
+} lagkv_status;
+
+typedef enum { LAGKV_F32 = 0, LAGKV_BF16 = 1 } lagkv_dtype;
+
+typedef enum {
+  LAGKV_SCORE_LAG = 0,   /* Eq. 7-11: min/max from the next chunk                       */
+  LAGKV_SCORE_LOCAL = 1, /* Eq. 14-15 (Scoring Methods ablation): min/max from the chunk */
+  LAGKV_SCORE_L2 = 2     /* Eq. 16: score = -||K_t||_2, V unused                         */
+} lagkv_variant;
+
+/* Statement of the problem: shape of the cache and the three knobs of the method. */
+typedef struct {
+  int32_t B, H, D;     /* batch (x layers), KV heads, head dimension (D >= 1; D >= 2 if std_ddof=1) */
+  int32_t S, L;        /* sink size S >= 0 and lag size L >= 1 (bullets 2-4 of subsection LagKV)     */
+  double r;            /* retention ratio in (0, 1]; k = floor(r*L) must be >= 1 ("only rL tokens")  */
+  int32_t dtype;       /* lagkv_dtype of K and V                                                     */
+  int32_t variant;     /* lagkv_variant                                                              */
+  int32_t std_ddof;    /* divisor of the channel-wise std is D - std_ddof; 1 (default reading) or 0  */
+  int32_t reserved;    /* must be 0                                                                  */
+  int64_t stride_b, stride_h, stride_t; /* INPUT strides in elements; 0 = dense [B,H,T,D]           */
+} lagkv_params;
+
+/* Partition of a cache of T rows whose first n_static rows are final. */
+typedef struct {
+  int64_t n_chunks; /* full L-chunks after the static part                                  */
+  int64_t n_scored; /* chunks that have a reference chunk = n_chunks - 1, or 0 if T-n_static < 2L */
+  int64_t rem;      /* (T - n_static) mod L; these rows join the sliding window             */
+  int64_t k;        /* rows kept per scored chunk                                           */
+  int64_t T_out;    /* length after compression (Eq. 12 when n_static == S); T if no-op     */
+} lagkv_plan_t;
+
+/*
+ * Host-only arithmetic of the partition bullets and Eq. 12-13.  n_static < 0
+ * means "fresh cache" (n_static = S).  When T - n_static < 2L the pass is a
+ * no-op ("skip the compression"): n_scored = 0 and T_out = T; not an error.
+ */
+int lagkv_plan(const lagkv_params* p, int64_t T, int64_t n_static, lagkv_plan_t* out);
+
+/*
+ * Device workspace, in bytes, that lagkv_score / lagkv_compress /
+ * lagkv_append_and_compress need for these parameters and T rows (for append:
+ * T = cache capacity).  0 when the fused kernels serve the shape; the
+ * three-kernel path used for unaligned or unusual shapes stages scores and
+ * kept positions there.  Returns 0 on invalid parameters as well.
+ */
+size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T);
+
+/*
+ * Eq. 7-11: scores of every scored chunk.
+ *   K, V    [B,H,T,D] device, dtype p->dtype (V may be NULL for LAGKV_SCORE_L2)
+ *   scores  [B,H,n_scored*L] device fp32, dense; entry j of a stream belongs to
+ *           row S + j.  Within a chunk the scores are softmax(std(Kbar)) +
+ *           softmax(std(Vbar)) and sum to 2.
+ * A reference channel with max == min contributes 0 to every token.
+ * n_scored == 0: returns LAGKV_OK and writes nothing.
+ */
+int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T,
+                float* scores, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Per-chunk, per-head top-k ("use the top-K strategy to select tokens in each
+ * partition and each head").
+ *   scores  [B,H,n_scored*L] device fp32 as written by lagkv_score
+ *   kept    [B,H,n_scored,k] device int32: absolute row positions (S + p*L + t)
+ *           of the k highest scores of chunk p, ASCENDING.  Equal scores: the
+ *           lower position wins.
+ */
+int lagkv_select(const lagkv_params* p, const float* scores, int64_t T, int32_t* kept,
+                 void* hip_stream);
+
+/*
+ * The whole pass: score, select, compact.
+ *   K_out, V_out  [B,H,T_out,D] device, dense, same dtype; row order: the S sink
+ *                 rows, the kept rows of chunk 0, 1, ... (ascending position),
+ *                 then the window rows S + n_scored*L .. T-1.  Bit copies.
+ *   idx_out       [B,H,T_out] device int32 source row of every output row, or NULL
+ *   scores_out    [B,H,n_scored*L] device fp32 as lagkv_score, or NULL
+ * Inputs and outputs must not overlap.  No-op case (T - S < 2L): copies the
+ * input (T_out = T).
+ */
+int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t T,
+                   void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Decode-time cache under recursive compression ("recursively compressing KV
+ * cache in both prefill and decode").  All buffers are caller-owned device
+ * memory, dense [B,H,capacity,D] (p->stride_* describe K_new/V_new only).
+ * The four counters are host integers, identical for every stream, and are
+ * updated by lagkv_append_and_compress before it returns (the device work is
+ * only enqueued).  A zero-initialised struct with buffers set is an empty cache.
+ */
+typedef struct {
+  void* K;          /* [B,H,capacity,D]                                              */
+  void* V;          /* [B,H,capacity,D]                                              */
+  int32_t* pos;     /* [B,H,capacity] original position of every row held, or NULL   */
+  int64_t capacity; /* rows per stream                                               */
+  int64_t n_static; /* rows that are final: min(n_seen,S) + k * (chunks compressed)  */
+  int64_t n_tail;   /* uncompressed rows after them; < 2L between calls              */
+  int64_t n_seen;   /* tokens appended so far                                        */
+} lagkv_cache;
+
+/*
+ * Append n_new rows per stream (K_new, V_new: [B,H,n_new,D] with p->stride_*,
+ * 0 = dense), then, while the tail holds at least 2L rows, score its oldest L
+ * rows against the next L, keep k of them right after the static part and
+ * slide the remaining tail down.  Equivalent to lagkv_compress on the whole
+ * history.  n_new = 0 is allowed.  Needs capacity >= n_static + n_tail + n_new.
+ * The cache of lagkv_compress's output is: n_static = S + k*n_scored,
+ * n_tail = L + rem, n_seen = T.
+ */
+int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const void* K_new,
+                              const void* V_new, int64_t n_new, void* ws, size_t ws_bytes,
+                              void* hip_stream);
+
+/*
+ * Launch tuning for benchmarks and tests (process-global, not thread-safe
+ * against concurrent calls).  key: LAGKV_TUNE_*; value 0 restores the
+ * automatic choice.  Returns LAGKV_EINVAL for an unknown key or a value the
+ * kernels do not support.
+ */
+enum {
+  LAGKV_TUNE_PATH = 0,       /* 0 auto, 1 force the fused kernels (error if unsupported), 2 force the three-kernel path */
+  LAGKV_TUNE_WAVES = 1,      /* wavefronts cooperating on one chunk in the fused kernel: 1,2,4,8 */
+  LAGKV_TUNE_SEGMENTS = 2,   /* segments each stream is cut into by the fused kernel (>= 1)         */
+  LAGKV_TUNE_COUNT = 3
+};
+int lagkv_tune(int key, int64_t value);
+
+/* Static, human readable text for a lagkv_status. */
+const char* lagkv_strerror(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int lagkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAGKV_H */

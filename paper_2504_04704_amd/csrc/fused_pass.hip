@@ -1,0 +1,601 @@
+// Fused LagKV kernels for gfx950: one streaming read of K and V per pass.
+//
+// Row layout: a token row (D channels) is 16*LPR bytes and is held by LPR
+// consecutive lanes, 16 bytes each, so one wave64 load instruction fetches 64/LPR
+// whole rows and the per-token channel reductions of Eq. 10 are DPP reductions over
+// LPR lanes.  The per-channel min/max of Eq. 7-8 accumulate in registers down the
+// rows a lane visits and are folded across row groups and wavefronts once per chunk.
+//
+// fused_pass_kernel walks a segment of one stream BACKWARDS: while chunk p is
+// scored with the statistics of chunk p+1 (already in registers) its own min/max are
+// collected for chunk p-1, so every input byte is fetched from HBM once.  The only
+// extra read is one statistics-only chunk per segment.  After a chunk is scored one
+// wavefront runs the chunk softmax (Eq. 10-11) and the top-k; then all wavefronts
+// copy the kept rows (a re-read that is served by the caches) to the dense output.
+#include "lagkv_internal.hpp"
+#include "wave_ops.hpp"
+
+namespace lagkv {
+
+struct F32 {
+  static constexpr int VEC = 4;
+};
+struct BF16 {
+  static constexpr int VEC = 8;
+};
+
+template <typename ET>
+__device__ __forceinline__ void unpack(const uint4& q, float (&x)[ET::VEC]) {
+  if constexpr (ET::VEC == 4) {
+    x[0] = __uint_as_float(q.x);
+    x[1] = __uint_as_float(q.y);
+    x[2] = __uint_as_float(q.z);
+    x[3] = __uint_as_float(q.w);
+  } else {  // bf16 -> fp32 is a 16-bit shift; element 2i is the low half of word i
+    x[0] = __uint_as_float(q.x << 16);
+    x[1] = __uint_as_float(q.x & 0xffff0000u);
+    x[2] = __uint_as_float(q.y << 16);
+    x[3] = __uint_as_float(q.y & 0xffff0000u);
+    x[4] = __uint_as_float(q.z << 16);
+    x[5] = __uint_as_float(q.z & 0xffff0000u);
+    x[6] = __uint_as_float(q.w << 16);
+    x[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+}
+
+__device__ __forceinline__ uint4 ld16(const char* p) {
+  return *reinterpret_cast<const uint4*>(p);
+}
+__device__ __forceinline__ void st16(char* p, const uint4& v) {
+  *reinterpret_cast<uint4*>(p) = v;
+}
+
+// Running per-channel min/max of the lane's VEC channels (Eq. 7-8), K and V.
+template <int VEC>
+struct ChanStats {
+  float mnK[VEC], mxK[VEC], mnV[VEC], mxV[VEC];
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      mnK[j] = INFINITY;
+      mxK[j] = -INFINITY;
+      mnV[j] = INFINITY;
+      mxV[j] = -INFINITY;
+    }
+  }
+};
+
+// Reference statistics in the form the normalisation of Eq. 9 consumes:
+// zbar = (x - mn) * iv with iv = 1/(max-min), or 0 for a constant channel.
+// bias = sum_j -(mn_j*iv_j) seeds the (accuracy-insensitive) mean accumulation.
+template <int VEC>
+struct RefStats {
+  float mnK[VEC], ivK[VEC], mnV[VEC], ivV[VEC];
+  float biasK, biasV;
+  __device__ __forceinline__ void from(const ChanStats<VEC>& s) {
+    biasK = 0.f;
+    biasV = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      mnK[j] = s.mnK[j];
+      ivK[j] = (s.mxK[j] > s.mnK[j]) ? 1.0f / (s.mxK[j] - s.mnK[j]) : 0.f;
+      mnV[j] = s.mnV[j];
+      ivV[j] = (s.mxV[j] > s.mnV[j]) ? 1.0f / (s.mxV[j] - s.mnV[j]) : 0.f;
+      biasK -= mnK[j] * ivK[j];
+      biasV -= mnV[j] * ivV[j];
+    }
+  }
+};
+
+// Standard deviation over the D channels of one normalised token (Eq. 9-10).
+// Two passes: the mean first (any error in it only enters the variance to second
+// order, so the cheap fma form is used), then the centred sum of squares from the
+// exactly subtracted (x - mn).
+template <int LPR, int VEC>
+__device__ __forceinline__ float token_spread(const float (&x)[VEC], const float (&mn)[VEC],
+                                              const float (&iv)[VEC], float bias, float inv_D,
+                                              float inv_dof) {
+  float s = bias;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
+  s = group_sum<LPR>(s);
+  const float mean = s * inv_D;
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    const float d = fmaf(x[j] - mn[j], iv[j], -mean);
+    ss = fmaf(d, d, ss);
+  }
+  ss = group_sum<LPR>(ss);
+  return sqrtf(ss * inv_dof);
+}
+
+struct Geometry {
+  int lane, wave, nw;  // lane in wave, wave in workgroup, waves per workgroup
+  int rl, cl;          // row within a wave step, 16-byte column slice
+  int rps;             // rows per workgroup step
+  int row0;            // first row this lane visits
+};
+
+template <int LPR>
+__device__ __forceinline__ Geometry make_geometry() {
+  Geometry g;
+  g.lane = threadIdx.x & 63;
+  g.wave = threadIdx.x >> 6;
+  g.nw = blockDim.x >> 6;
+  g.rl = g.lane / LPR;
+  g.cl = g.lane % LPR;
+  g.rps = g.nw * (kWave / LPR);
+  g.row0 = g.wave * (kWave / LPR) + g.rl;
+  return g;
+}
+
+// One pass over the L rows of a chunk.  STATS: fold the rows into `acc`.  SCORE:
+// write the spread of every token, normalised with `ref`, to sK/sV (LDS).
+// Rows past L are clamped to the last row (duplicates do not change min/max).
+template <typename ET, int LPR, bool STATS, bool SCORE>
+__device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const char* __restrict__ vp,
+                                           int64_t st, int L, const Geometry& g,
+                                           ChanStats<ET::VEC>& acc, const RefStats<ET::VEC>& ref,
+                                           float inv_D, float inv_dof, float* sK, float* sV) {
+  constexpr int VEC = ET::VEC;
+  constexpr int U = 4;
+  const int n_iter = (L + g.rps - 1) / g.rps;
+  const int64_t coff = (int64_t)g.cl * 16;
+  for (int it = 0; it < n_iter; it += U) {
+    uint4 kq[U], vq[U];
+    int r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      r[u] = g.row0 + (it + u) * g.rps;
+      const int rr = r[u] < L ? r[u] : L - 1;
+      kq[u] = ld16(kp + (int64_t)rr * st + coff);
+      vq[u] = ld16(vp + (int64_t)rr * st + coff);
+    }
+#pragma unroll
+    for (int u = 0; u < U; u += 2) {
+      float x0[VEC], x1[VEC];
+      float sgK0 = 0.f, sgK1 = 0.f, sgV0 = 0.f, sgV1 = 0.f;
+      unpack<ET>(kq[u], x0);
+      unpack<ET>(kq[u + 1], x1);
+      if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          acc.mnK[j] = fminf(fminf(acc.mnK[j], x0[j]), x1[j]);
+          acc.mxK[j] = fmaxf(fmaxf(acc.mxK[j], x0[j]), x1[j]);
+        }
+      }
+      if constexpr (SCORE) {
+        sgK0 = token_spread<LPR, VEC>(x0, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
+        sgK1 = token_spread<LPR, VEC>(x1, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
+      }
+      unpack<ET>(vq[u], x0);
+      unpack<ET>(vq[u + 1], x1);
+      if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          acc.mnV[j] = fminf(fminf(acc.mnV[j], x0[j]), x1[j]);
+          acc.mxV[j] = fmaxf(fmaxf(acc.mxV[j], x0[j]), x1[j]);
+        }
+      }
+      if constexpr (SCORE) {
+        sgV0 = token_spread<LPR, VEC>(x0, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
+        sgV1 = token_spread<LPR, VEC>(x1, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
+        if (g.cl == 0) {
+          if (r[u] < L) {
+            sK[r[u]] = sgK0;
+            sV[r[u]] = sgV0;
+          }
+          if (r[u + 1] < L) {
+            sK[r[u + 1]] = sgK1;
+            sV[r[u + 1]] = sgV1;
+          }
+        }
+      }
+    }
+  }
+}
+
+// Fold the per-lane partial min/max across the row groups of a wave and across the
+// wavefronts of the workgroup; every lane ends with the statistics of its own VEC
+// channels over the whole chunk.  Contains one __syncthreads(), which also publishes
+// the spreads written by scan_chunk.  statbuf: [nw][4][D] floats of LDS.
+template <int LPR, int VEC>
+__device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& g, float* statbuf,
+                                           int D) {
+#pragma unroll
+  for (int m = LPR; m < kWave; m <<= 1) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      acc.mnK[j] = fminf(acc.mnK[j], __shfl_xor(acc.mnK[j], m));
+      acc.mxK[j] = fmaxf(acc.mxK[j], __shfl_xor(acc.mxK[j], m));
+      acc.mnV[j] = fminf(acc.mnV[j], __shfl_xor(acc.mnV[j], m));
+      acc.mxV[j] = fmaxf(acc.mxV[j], __shfl_xor(acc.mxV[j], m));
+    }
+  }
+  if (g.nw > 1) {
+    if (g.rl == 0) {
+      float* w = statbuf + (size_t)g.wave * 4 * D + g.cl * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        w[j] = acc.mnK[j];
+        w[D + j] = acc.mxK[j];
+        w[2 * D + j] = acc.mnV[j];
+        w[3 * D + j] = acc.mxV[j];
+      }
+    }
+    __syncthreads();
+    for (int w = 0; w < g.nw; ++w) {
+      const float* rd = statbuf + (size_t)w * 4 * D + g.cl * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        acc.mnK[j] = fminf(acc.mnK[j], rd[j]);
+        acc.mxK[j] = fmaxf(acc.mxK[j], rd[j + D]);
+        acc.mnV[j] = fminf(acc.mnV[j], rd[j + 2 * D]);
+        acc.mxV[j] = fmaxf(acc.mxV[j], rd[j + 3 * D]);
+      }
+    }
+  } else {
+    __syncthreads();
+  }
+}
+
+// dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane.
+template <int LPR>
+__device__ __forceinline__ void copy_rows_kv(const char* __restrict__ ks, const char* __restrict__ vs,
+                                             int64_t sst, char* __restrict__ kd,
+                                             char* __restrict__ vd, int64_t dst_st, int64_t nrows,
+                                             int tid, int nthreads) {
+  const int cl = tid % LPR;
+  const int64_t ng = nthreads / LPR;
+  for (int64_t r = tid / LPR; r < nrows; r += ng) {
+    const uint4 a = ld16(ks + r * sst + cl * 16);
+    const uint4 b = ld16(vs + r * sst + cl * 16);
+    st16(kd + r * dst_st + cl * 16, a);
+    st16(vd + r * dst_st + cl * 16, b);
+  }
+}
+
+struct LdsLayout {
+  int off_sK, off_sV, off_list, off_stat, total;  // in bytes
+};
+__host__ __device__ inline LdsLayout lds_layout(int D, int L, int k, int nw) {
+  LdsLayout l;
+  const int lp = (L + 3) & ~3;
+  const int kp = (k + 3) & ~3;
+  l.off_sK = 0;
+  l.off_sV = lp * 4;
+  l.off_list = 2 * lp * 4;
+  l.off_stat = l.off_list + kp * 4;
+  l.total = l.off_stat + (nw > 1 ? nw * 4 * D * 4 : 0);
+  return l;
+}
+
+template <typename ET, int LPR>
+__global__ void __launch_bounds__(512) fused_pass_kernel(const PassArgs a) {
+  constexpr int VEC = ET::VEC;
+  extern __shared__ float4 lds_raw[];
+  char* lds = reinterpret_cast<char*>(lds_raw);
+  const Geometry g = make_geometry<LPR>();
+  const LdsLayout lay = lds_layout(a.D, a.L, a.k, g.nw);
+  float* sK = reinterpret_cast<float*>(lds + lay.off_sK);
+  float* sV = reinterpret_cast<float*>(lds + lay.off_sV);
+  uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int64_t stream = blockIdx.x / a.nseg;
+  const int seg = blockIdx.x % a.nseg;
+  const int64_t b = stream / a.H, h = stream % a.H;
+  const char* kin = a.K + b * a.sb + h * a.sh;
+  const char* vin = a.V + b * a.sb + h * a.sh;
+  const int64_t rowbytes = (int64_t)LPR * 16;
+  const bool gather = a.K_out != nullptr;
+  char* kout = gather ? a.K_out + stream * a.T_out * rowbytes : nullptr;
+  char* vout = gather ? a.V_out + stream * a.T_out * rowbytes : nullptr;
+  int32_t* iout = (gather && a.idx_out) ? a.idx_out + stream * a.T_out : nullptr;
+  float* sout = a.scores ? a.scores + stream * a.n_s * a.L : nullptr;
+  const int L = a.L, k = a.k, S = a.S;
+  const float inv_D = 1.0f / (float)a.D;
+  const float inv_dof = 1.0f / (float)(a.D - a.ddof);
+
+  for (int i = tid; i < k; i += nthreads) list[i] = 0;
+
+  // sink rows and the sliding window (last full chunk + remainder) are plain copies
+  if (gather && seg == 0 && S > 0) {
+    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, tid, nthreads);
+    if (iout)
+      for (int i = tid; i < S; i += nthreads) iout[i] = i;
+  }
+  if (gather && seg == a.nseg - 1) {
+    const int64_t w0 = S + a.n_s * L, o0 = S + a.n_s * k, nwin = a.T - w0;
+    copy_rows_kv<LPR>(kin + w0 * a.st, vin + w0 * a.st, a.st, kout + o0 * rowbytes,
+                      vout + o0 * rowbytes, rowbytes, nwin, tid, nthreads);
+    if (iout)
+      for (int64_t i = tid; i < nwin; i += nthreads) iout[o0 + i] = (int32_t)(w0 + i);
+  }
+
+  const int64_t p0 = (int64_t)seg * a.n_s / a.nseg;
+  const int64_t p1 = (int64_t)(seg + 1) * a.n_s / a.nseg;
+
+  ChanStats<VEC> acc;
+  RefStats<VEC> ref;
+  const bool local = a.variant == 1;  // Eq. 14-15: statistics from the chunk itself
+  if (!local) {
+    // statistics of the chunk after the segment: the first reference
+    acc.reset();
+    const int64_t c = (S + p1 * L) * a.st;
+    scan_chunk<ET, LPR, true, false>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
+    fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
+    ref.from(acc);
+    __syncthreads();  // statbuf is rewritten by the next fold
+  }
+
+  for (int64_t p = p1 - 1; p >= p0; --p) {
+    const int64_t c = (S + p * L) * a.st;
+    acc.reset();
+    if (local) {
+      scan_chunk<ET, LPR, true, false>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
+      fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
+      ref.from(acc);
+      scan_chunk<ET, LPR, false, true>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
+      __syncthreads();
+    } else {
+      scan_chunk<ET, LPR, true, true>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
+      fold_stats<LPR, VEC>(acc, g, statbuf, a.D);  // barrier inside: spreads are visible
+      ref.from(acc);                               // chunk p is the reference of chunk p-1
+    }
+    if (g.wave == 0) {
+      wave_chunk_softmax(sK, sV, L, sout ? sout + p * L : nullptr, g.lane);
+      if (gather) wave_select_any(sK, L, k, list, g.lane);
+    }
+    __syncthreads();
+    if (gather) {
+      const char* ksrc = kin + c;
+      const char* vsrc = vin + c;
+      char* kd = kout + (S + p * k) * rowbytes;
+      char* vd = vout + (S + p * k) * rowbytes;
+      const int64_t coff = (int64_t)g.cl * 16;
+      for (int s0 = g.row0; s0 < k; s0 += 2 * g.rps) {
+        const int s1 = s0 + g.rps;
+        const int64_t t0 = list[s0];
+        const int64_t t1 = list[s1 < k ? s1 : s0];
+        const uint4 ka = ld16(ksrc + t0 * a.st + coff);
+        const uint4 va = ld16(vsrc + t0 * a.st + coff);
+        const uint4 kb = ld16(ksrc + t1 * a.st + coff);
+        const uint4 vb = ld16(vsrc + t1 * a.st + coff);
+        st16(kd + s0 * rowbytes + coff, ka);
+        st16(vd + s0 * rowbytes + coff, va);
+        if (s1 < k) {
+          st16(kd + s1 * rowbytes + coff, kb);
+          st16(vd + s1 * rowbytes + coff, vb);
+        }
+      }
+      if (iout)
+        for (int i = tid; i < k; i += nthreads)
+          iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Decode-time variant: one workgroup per stream, in place.  Appends the new rows,
+// then compresses `rounds` chunks of the tail front to back (each against the raw
+// next chunk) and finally slides what is left of the tail down behind the kept rows.
+// Every in-place move goes destination <= source in ascending order, one register
+// staged batch at a time: a batch is loaded, the workgroup synchronises, the batch is
+// stored; the rows a later batch reads lie above everything stored so far.
+// ---------------------------------------------------------------------------------
+template <int LPR>
+__device__ __forceinline__ void move_rows_down(char* kc, char* vc, int32_t* pc, int64_t src0,
+                                               int64_t dst0, int64_t nrows, const Geometry& g,
+                                               int tid, int nthreads) {
+  const int64_t rowbytes = (int64_t)LPR * 16, coff = (int64_t)g.cl * 16;
+  constexpr int UB = 4;
+  const int64_t batch = (int64_t)UB * g.rps;
+  for (int64_t r0 = 0; r0 < nrows; r0 += batch) {
+    uint4 kq[UB], vq[UB];
+    int32_t pv[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int64_t r = r0 + u * g.rps + g.row0;
+      if (r < nrows) {
+        kq[u] = ld16(kc + (src0 + r) * rowbytes + coff);
+        vq[u] = ld16(vc + (src0 + r) * rowbytes + coff);
+        if (pc && g.cl == 0) pv[u] = pc[src0 + r];
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int64_t r = r0 + u * g.rps + g.row0;
+      if (r < nrows) {
+        st16(kc + (dst0 + r) * rowbytes + coff, kq[u]);
+        st16(vc + (dst0 + r) * rowbytes + coff, vq[u]);
+        if (pc && g.cl == 0) pc[dst0 + r] = pv[u];
+      }
+    }
+  }
+  (void)tid;
+  (void)nthreads;
+}
+
+template <typename ET, int LPR>
+__global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
+  constexpr int VEC = ET::VEC;
+  extern __shared__ float4 lds_raw[];
+  char* lds = reinterpret_cast<char*>(lds_raw);
+  const Geometry g = make_geometry<LPR>();
+  const LdsLayout lay = lds_layout(a.D, a.L, a.k, g.nw);
+  float* sK = reinterpret_cast<float*>(lds + lay.off_sK);
+  float* sV = reinterpret_cast<float*>(lds + lay.off_sV);
+  uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int64_t stream = blockIdx.x;
+  const int64_t b = stream / a.H, h = stream % a.H;
+  const int64_t rowbytes = (int64_t)LPR * 16;
+  char* kc = a.K + stream * a.capacity * rowbytes;
+  char* vc = a.V + stream * a.capacity * rowbytes;
+  int32_t* pc = a.pos ? a.pos + stream * a.capacity : nullptr;
+  const int L = a.L, k = a.k;
+  const float inv_D = 1.0f / (float)a.D;
+  const float inv_dof = 1.0f / (float)(a.D - a.ddof);
+
+  for (int i = tid; i < k; i += nthreads) list[i] = 0;
+
+  // 1. append
+  const int64_t end0 = a.n_static + a.n_tail;
+  if (a.n_new > 0) {
+    const char* kn = a.K_new + b * a.nsb + h * a.nsh;
+    const char* vn = a.V_new + b * a.nsb + h * a.nsh;
+    copy_rows_kv<LPR>(kn, vn, a.nst, kc + end0 * rowbytes, vc + end0 * rowbytes, rowbytes, a.n_new,
+                      tid, nthreads);
+    if (pc)
+      for (int64_t i = tid; i < a.n_new; i += nthreads) pc[end0 + i] = (int32_t)(a.n_seen + i);
+  }
+  if (a.rounds <= 0) return;
+  __syncthreads();
+
+  // static boundary after the append (the sink fills up first)
+  const int64_t total = end0 + a.n_new;
+  int64_t base = a.n_static;
+  if (a.n_seen < a.S) {
+    const int64_t seen = a.n_seen + a.n_new;
+    base = seen < a.S ? seen : a.S;
+  }
+
+  ChanStats<VEC> acc;
+  RefStats<VEC> ref;
+  const int64_t coff = (int64_t)g.cl * 16;
+  for (int64_t j = 0; j < a.rounds; ++j) {
+    const int64_t cur = base + j * L;      // rows of the chunk (not yet moved)
+    const int64_t dst = base + j * k;      // where its kept rows go
+    acc.reset();
+    const int64_t refc = (a.variant == 1) ? cur : cur + L;  // Eq. 14-15 vs Eq. 7-8
+    scan_chunk<ET, LPR, true, false>(kc + refc * rowbytes, vc + refc * rowbytes, rowbytes, L, g, acc,
+                                     ref, inv_D, inv_dof, sK, sV);
+    fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
+    ref.from(acc);
+    scan_chunk<ET, LPR, false, true>(kc + cur * rowbytes, vc + cur * rowbytes, rowbytes, L, g, acc,
+                                     ref, inv_D, inv_dof, sK, sV);
+    __syncthreads();
+    if (g.wave == 0) {
+      wave_chunk_softmax(sK, sV, L, nullptr, g.lane);
+      wave_select_any(sK, L, k, list, g.lane);
+    }
+    __syncthreads();
+    // staged in-place gather of the kept rows
+    constexpr int UB = 4;
+    for (int s0 = 0; s0 < k; s0 += UB * g.rps) {
+      uint4 kq[UB], vq[UB];
+      int32_t pv[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int sl = s0 + u * g.rps + g.row0;
+        if (sl < k) {
+          const int64_t src = cur + list[sl];
+          kq[u] = ld16(kc + src * rowbytes + coff);
+          vq[u] = ld16(vc + src * rowbytes + coff);
+          if (pc && g.cl == 0) pv[u] = pc[src];
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int sl = s0 + u * g.rps + g.row0;
+        if (sl < k) {
+          st16(kc + (dst + sl) * rowbytes + coff, kq[u]);
+          st16(vc + (dst + sl) * rowbytes + coff, vq[u]);
+          if (pc && g.cl == 0) pc[dst + sl] = pv[u];
+        }
+      }
+    }
+    __syncthreads();  // list and statbuf are rewritten by the next round
+  }
+  // 3. slide the rest of the tail behind the kept rows
+  const int64_t src0 = base + a.rounds * L, dst0 = base + a.rounds * k;
+  if (src0 != dst0)
+    move_rows_down<LPR>(kc, vc, pc, src0, dst0, total - src0, g, tid, nthreads);
+}
+
+// ---------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+static int lanes_per_row(int D, int esize) {
+  const int64_t rb = (int64_t)D * esize;
+  switch (rb) {
+    case 64: return 4;
+    case 128: return 8;
+    case 256: return 16;
+    case 512: return 32;
+    default: return 0;
+  }
+}
+
+bool fused_supported(int D, int esize, int64_t sb, int64_t sh, int64_t st, const void* K,
+                     const void* V, const void* Ko, const void* Vo) {
+  if (lanes_per_row(D, esize) == 0) return false;
+  if ((sb | sh | st) & 15) return false;
+  return aligned16(K) && aligned16(V) && aligned16(Ko) && aligned16(Vo);
+}
+
+size_t fused_lds_bytes(int D, int L, int k, int nwaves) {
+  return (size_t)lds_layout(D, L, k, nwaves).total;
+}
+
+template <typename ET>
+static hipError_t launch_pass_t(const PassArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
+                                hipStream_t s) {
+  switch (lpr) {
+    case 4: fused_pass_kernel<ET, 4><<<grid, block, lds, s>>>(a); break;
+    case 8: fused_pass_kernel<ET, 8><<<grid, block, lds, s>>>(a); break;
+    case 16: fused_pass_kernel<ET, 16><<<grid, block, lds, s>>>(a); break;
+    case 32: fused_pass_kernel<ET, 32><<<grid, block, lds, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_pass(const PassArgs& a, hipStream_t s) {
+  const int lpr = lanes_per_row(a.D, a.esize);
+  const int64_t streams = (int64_t)a.B * a.H;
+  const int64_t nblocks = streams * a.nseg;
+  if (lpr == 0 || nblocks <= 0 || nblocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  const size_t lds = fused_lds_bytes(a.D, a.L, a.k, a.nwaves);
+  if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);
+  return a.esize == 4 ? launch_pass_t<F32>(a, lpr, grid, block, lds, s)
+                      : launch_pass_t<BF16>(a, lpr, grid, block, lds, s);
+}
+
+template <typename ET>
+static hipError_t launch_append_t(const AppendArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
+                                  hipStream_t s) {
+  switch (lpr) {
+    case 4: fused_append_kernel<ET, 4><<<grid, block, lds, s>>>(a); break;
+    case 8: fused_append_kernel<ET, 8><<<grid, block, lds, s>>>(a); break;
+    case 16: fused_append_kernel<ET, 16><<<grid, block, lds, s>>>(a); break;
+    case 32: fused_append_kernel<ET, 32><<<grid, block, lds, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s) {
+  const int lpr = lanes_per_row(a.D, a.esize);
+  const int64_t streams = (int64_t)a.B * a.H;
+  if (lpr == 0 || streams <= 0 || streams > 0x7fffffffLL) return hipErrorInvalidValue;
+  const size_t lds = fused_lds_bytes(a.D, a.L, a.k, a.nwaves);
+  if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)streams), block(a.nwaves * kWave);
+  return a.esize == 4 ? launch_append_t<F32>(a, lpr, grid, block, lds, s)
+                      : launch_append_t<BF16>(a, lpr, grid, block, lds, s);
+}
+
+}  // namespace lagkv

@@ -1,0 +1,472 @@
+// C ABI of the LagKV compression pass (see include/lagkv.h): host-side validation,
+// the partition arithmetic of Eq. 12-13, path choice and kernel launches.
+#include "lagkv.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "lagkv_internal.hpp"
+
+using namespace lagkv;
+
+namespace {
+
+int64_t g_tune[LAGKV_TUNE_COUNT] = {0, 0, 0};
+
+constexpr int64_t kMaxRows = 0x7fffffffLL;  // positions are int32
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Norm {  // validated, normalised parameters
+  int B, H, D, S, L, k, esize, ddof, variant;
+  int64_t streams;
+  int64_t rowbytes;
+};
+
+int validate(const lagkv_params* p, Norm* n) {
+  if (!p) return LAGKV_EINVAL;
+  if (p->dtype != LAGKV_F32 && p->dtype != LAGKV_BF16) return LAGKV_EDTYPE;
+  if (p->variant < LAGKV_SCORE_LAG || p->variant > LAGKV_SCORE_L2) return LAGKV_EDTYPE;
+  if (p->reserved != 0) return LAGKV_EINVAL;
+  if (p->std_ddof != 0 && p->std_ddof != 1) return LAGKV_EINVAL;
+  if (p->B < 1 || p->H < 1 || p->D < 1) return LAGKV_ESHAPE;
+  if (p->std_ddof == 1 && p->D < 2 && p->variant != LAGKV_SCORE_L2) return LAGKV_ESHAPE;
+  if (p->S < 0 || p->L < 1) return LAGKV_EINVAL;
+  if (!(p->r > 0.0) || !(p->r <= 1.0)) return LAGKV_EINVAL;  // also rejects NaN
+  const double kd = std::floor(p->r * (double)p->L);
+  if (kd < 1.0) return LAGKV_EINVAL;
+  if (p->stride_b < 0 || p->stride_h < 0 || p->stride_t < 0) return LAGKV_ESHAPE;
+  n->B = p->B;
+  n->H = p->H;
+  n->D = p->D;
+  n->S = p->S;
+  n->L = p->L;
+  n->k = (int)kd;
+  n->esize = p->dtype == LAGKV_F32 ? 4 : 2;
+  n->ddof = p->std_ddof;
+  n->variant = p->variant;
+  n->streams = (int64_t)p->B * p->H;
+  n->rowbytes = (int64_t)p->D * n->esize;
+  if (n->streams > (1 << 24)) return LAGKV_ESHAPE;
+  return LAGKV_OK;
+}
+
+void plan_of(const Norm& n, int64_t T, int64_t n_static, lagkv_plan_t* out) {
+  const int64_t rest = T - n_static;
+  out->k = n.k;
+  if (rest < 2 * (int64_t)n.L) {  // "skip the compression"
+    const int64_t r = rest > 0 ? rest : 0;
+    out->n_chunks = r / n.L;
+    out->rem = r % n.L;
+    out->n_scored = 0;
+    out->T_out = T;
+    return;
+  }
+  out->n_chunks = rest / n.L;
+  out->rem = rest % n.L;
+  out->n_scored = out->n_chunks - 1;  // the last chunk has no reference
+  out->T_out = n_static + (int64_t)n.k * out->n_scored + n.L + out->rem;  // Eq. 12
+}
+
+// Input strides in bytes; 0 means dense [B,H,T,D].
+int strides_of(const lagkv_params* p, const Norm& n, int64_t T, int64_t* sb, int64_t* sh,
+               int64_t* st) {
+  const int64_t t = p->stride_t ? p->stride_t : n.D;
+  const int64_t h = p->stride_h ? p->stride_h : t * T;
+  const int64_t b = p->stride_b ? p->stride_b : h * n.H;
+  if (t < n.D) return LAGKV_ESHAPE;
+  *st = t * n.esize;
+  *sh = h * n.esize;
+  *sb = b * n.esize;
+  return LAGKV_OK;
+}
+
+bool shape_fused(const Norm& n, int64_t sb, int64_t sh, int64_t st) {
+  if (n.variant == LAGKV_SCORE_L2) return false;
+  if (n.rowbytes != 64 && n.rowbytes != 128 && n.rowbytes != 256 && n.rowbytes != 512) return false;
+  return ((sb | sh | st) & 15) == 0;
+}
+
+int pick_waves(const Norm& n) {
+  int nw = g_tune[LAGKV_TUNE_WAVES] ? (int)g_tune[LAGKV_TUNE_WAVES] : 4;
+  while (nw > 1 && fused_lds_bytes(n.D, n.L, n.k, nw) > (size_t)kMaxLdsBytes) nw >>= 1;
+  return nw;
+}
+
+bool fused_fits(const Norm& n) { return fused_lds_bytes(n.D, n.L, n.k, 1) <= (size_t)kMaxLdsBytes; }
+
+bool staged_fits(const Norm& n) {
+  return staged_score_lds_bytes(n.D, n.L) <= (size_t)kMaxLdsBytes &&
+         ((size_t)n.L + n.k) * 4 <= (size_t)kMaxLdsBytes;
+}
+
+int pick_segments(const Norm& n, int64_t n_s) {
+  int64_t nseg;
+  if (g_tune[LAGKV_TUNE_SEGMENTS]) {
+    nseg = g_tune[LAGKV_TUNE_SEGMENTS];
+  } else {
+    // enough workgroups to fill 256 CUs several times over, segments of >= 8 chunks
+    nseg = (2048 + n.streams - 1) / n.streams;
+    const int64_t cap = n_s / 8 > 1 ? n_s / 8 : 1;
+    if (nseg > cap) nseg = cap;
+  }
+  if (nseg > n_s) nseg = n_s;
+  if (nseg < 1) nseg = 1;
+  return (int)nseg;
+}
+
+// Workspace of the three-kernel path for one pass: [scores][kept]
+struct StagedWs {
+  size_t off_scores, off_kept, total;
+};
+StagedWs staged_ws(const Norm& n, int64_t n_s, bool need_scores) {
+  StagedWs w;
+  w.off_scores = 0;
+  const size_t sc = need_scores ? align_up((size_t)n.streams * n_s * n.L * 4) : 0;
+  w.off_kept = sc;
+  w.total = sc + align_up((size_t)n.streams * n_s * n.k * 4);
+  return w;
+}
+
+// Workspace of the three-kernel append: [scores][kept][stage K][stage V][stage pos]
+struct AppendWs {
+  size_t off_scores, off_kept, off_k, off_v, off_pos, total;
+};
+AppendWs append_ws(const Norm& n, int64_t q, int64_t rows_staged) {
+  AppendWs w;
+  size_t o = 0;
+  w.off_scores = o;
+  o += align_up((size_t)n.streams * q * n.L * 4);
+  w.off_kept = o;
+  o += align_up((size_t)n.streams * q * n.k * 4);
+  w.off_k = o;
+  o += align_up((size_t)n.streams * rows_staged * n.rowbytes);
+  w.off_v = o;
+  o += align_up((size_t)n.streams * rows_staged * n.rowbytes);
+  w.off_pos = o;
+  o += align_up((size_t)n.streams * rows_staged * 4);
+  w.total = o;
+  return w;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? LAGKV_OK : LAGKV_EHIP; }
+
+bool aligned_to(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+void fill_pass(PassArgs* a, const Norm& n, const void* K, const void* V, int64_t T,
+               const lagkv_plan_t& pl, int64_t sb, int64_t sh, int64_t st) {
+  std::memset(a, 0, sizeof(*a));
+  a->K = (const char*)K;
+  a->V = (const char*)V;
+  a->sb = sb;
+  a->sh = sh;
+  a->st = st;
+  a->T = T;
+  a->T_out = pl.T_out;
+  a->n_s = pl.n_scored;
+  a->B = n.B;
+  a->H = n.H;
+  a->D = n.D;
+  a->S = n.S;
+  a->L = n.L;
+  a->k = n.k;
+  a->esize = n.esize;
+  a->ddof = n.ddof;
+  a->variant = n.variant;
+  a->nseg = 1;
+  a->nwaves = 4;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lagkv_plan(const lagkv_params* p, int64_t T, int64_t n_static, lagkv_plan_t* out) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (!out) return LAGKV_EINVAL;
+  if (T < 0 || T > kMaxRows) return LAGKV_ESHAPE;
+  if (n_static < 0) n_static = n.S;
+  if (n_static > T && T >= n.S) return LAGKV_EINVAL;
+  plan_of(n, T, n_static, out);
+  return LAGKV_OK;
+}
+
+size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T) {
+  Norm n;
+  if (validate(p, &n) != LAGKV_OK || T < 1 || T > kMaxRows) return 0;
+  int64_t sb, sh, st;
+  if (strides_of(p, n, T, &sb, &sh, &st) != LAGKV_OK) return 0;
+  const bool fused = g_tune[LAGKV_TUNE_PATH] != 2 && shape_fused(n, sb, sh, st) && fused_fits(n);
+  if (fused) return 0;
+  // one pass over T rows, and an append into a cache of capacity T
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  const size_t pass = staged_ws(n, pl.n_scored > 0 ? pl.n_scored : 1, true).total;
+  const size_t app = append_ws(n, T / n.L + 1, T).total;
+  return pass > app ? pass : app;
+}
+
+int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T, float* scores,
+                void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (T < 1 || T > kMaxRows) return LAGKV_ESHAPE;
+  if (!K || (!V && n.variant != LAGKV_SCORE_L2)) return LAGKV_EINVAL;
+  if (!aligned_to(K, n.esize) || !aligned_to(V, n.esize)) return LAGKV_EINVAL;
+  int64_t sb, sh, st;
+  rc = strides_of(p, n, T, &sb, &sh, &st);
+  if (rc != LAGKV_OK) return rc;
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  if (pl.n_scored == 0) return LAGKV_OK;
+  if (!scores) return LAGKV_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  PassArgs a;
+  fill_pass(&a, n, K, V, T, pl, sb, sh, st);
+  a.scores = scores;
+  const int64_t force = g_tune[LAGKV_TUNE_PATH];
+  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
+                        fused_supported(n.D, n.esize, sb, sh, st, K, V, nullptr, nullptr);
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != 2) {
+    a.nwaves = pick_waves(n);
+    a.nseg = pick_segments(n, pl.n_scored);
+    return hip_status(launch_fused_pass(a, s));
+  }
+  if (!staged_fits(n)) return LAGKV_ESHAPE;
+  return hip_status(launch_staged_score(a, n.S, scores, s));
+}
+
+int lagkv_select(const lagkv_params* p, const float* scores, int64_t T, int32_t* kept,
+                 void* hip_stream) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (T < 1 || T > kMaxRows) return LAGKV_ESHAPE;
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  if (pl.n_scored == 0) return LAGKV_OK;
+  if (!scores || !kept) return LAGKV_EINVAL;
+  if (((size_t)n.L + n.k) * 4 > (size_t)kMaxLdsBytes) return LAGKV_ESHAPE;
+  return hip_status(launch_select(scores, n.streams, pl.n_scored, n.L, n.k, n.S, kept,
+                                  (hipStream_t)hip_stream));
+}
+
+int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t T, void* K_out,
+                   void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes,
+                   void* hip_stream) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (T < 1 || T > kMaxRows) return LAGKV_ESHAPE;
+  if (!K || !V || !K_out || !V_out) return LAGKV_EINVAL;
+  if (!aligned_to(K, n.esize) || !aligned_to(V, n.esize) || !aligned_to(K_out, n.esize) ||
+      !aligned_to(V_out, n.esize))
+    return LAGKV_EINVAL;
+  int64_t sb, sh, st;
+  rc = strides_of(p, n, T, &sb, &sh, &st);
+  if (rc != LAGKV_OK) return rc;
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (pl.n_scored == 0) {  // nothing to compress: the output is the input
+    const int64_t osh = T * n.rowbytes, osb = osh * n.H;
+    hipError_t e = launch_copy_rows((const char*)K, sb, sh, st, (char*)K_out, osb, osh, n.rowbytes,
+                                    n.B, n.H, T, n.rowbytes, s);
+    if (e == hipSuccess)
+      e = launch_copy_rows((const char*)V, sb, sh, st, (char*)V_out, osb, osh, n.rowbytes, n.B, n.H,
+                           T, n.rowbytes, s);
+    if (e == hipSuccess && idx_out) e = launch_iota_rows(idx_out, n.streams, T, 0, T, 0, s);
+    return hip_status(e);
+  }
+  PassArgs a;
+  fill_pass(&a, n, K, V, T, pl, sb, sh, st);
+  a.K_out = (char*)K_out;
+  a.V_out = (char*)V_out;
+  a.idx_out = idx_out;
+  a.scores = scores_out;
+  const int64_t force = g_tune[LAGKV_TUNE_PATH];
+  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
+                        fused_supported(n.D, n.esize, sb, sh, st, K, V, K_out, V_out);
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != 2) {
+    a.nwaves = pick_waves(n);
+    a.nseg = pick_segments(n, pl.n_scored);
+    return hip_status(launch_fused_pass(a, s));
+  }
+  if (!staged_fits(n)) return LAGKV_ESHAPE;
+  const StagedWs w = staged_ws(n, pl.n_scored, scores_out == nullptr);
+  if (!ws || ws_bytes < w.total || !aligned_to(ws, 16)) return LAGKV_EWORKSPACE;
+  float* sc = scores_out ? scores_out : (float*)((char*)ws + w.off_scores);
+  int32_t* kept = (int32_t*)((char*)ws + w.off_kept);
+  hipError_t e = launch_staged_score(a, n.S, sc, s);
+  if (e == hipSuccess) e = launch_select(sc, n.streams, pl.n_scored, n.L, n.k, n.S, kept, s);
+  if (e == hipSuccess) e = launch_staged_gather(a, kept, s);
+  return hip_status(e);
+}
+
+int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void* K_new,
+                              const void* V_new, int64_t n_new, void* ws, size_t ws_bytes,
+                              void* hip_stream) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (!c || !c->K || !c->V) return LAGKV_EINVAL;
+  if (n_new < 0 || c->capacity < 1 || c->n_static < 0 || c->n_tail < 0 || c->n_seen < 0)
+    return LAGKV_EINVAL;
+  if (n_new > 0 && (!K_new || !V_new)) return LAGKV_EINVAL;
+  if (c->capacity > kMaxRows || c->n_seen + n_new > kMaxRows) return LAGKV_ESHAPE;
+  if (!aligned_to(c->K, n.esize) || !aligned_to(c->V, n.esize) || !aligned_to(K_new, n.esize) ||
+      !aligned_to(V_new, n.esize))
+    return LAGKV_EINVAL;
+  const int64_t held = c->n_static + c->n_tail;
+  if (held + n_new > c->capacity) return LAGKV_ECAPACITY;
+  int64_t sb = 0, sh = 0, st = 0;
+  if (n_new > 0) {
+    rc = strides_of(p, n, n_new, &sb, &sh, &st);
+    if (rc != LAGKV_OK) return rc;
+  }
+  // host arithmetic of the recursion: the sink fills first, then the tail is cut
+  // into L-chunks and all but the last full one are compressed
+  const int64_t total = held + n_new;
+  int64_t base = c->n_static;
+  if (c->n_seen < n.S) {
+    const int64_t seen = c->n_seen + n_new;
+    base = seen < n.S ? seen : n.S;
+  }
+  const int64_t tail = total - base;
+  const int64_t q = tail >= 2 * (int64_t)n.L ? tail / n.L - 1 : 0;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int64_t force = g_tune[LAGKV_TUNE_PATH];
+  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
+                        fused_supported(n.D, n.esize, sb, sh, st, c->K, c->V, K_new, V_new);
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  hipError_t e = hipSuccess;
+  if (fused_ok && force != 2) {
+    if (n_new > 0 || q > 0) {
+      AppendArgs a;
+      std::memset(&a, 0, sizeof(a));
+      a.K = (char*)c->K;
+      a.V = (char*)c->V;
+      a.pos = c->pos;
+      a.K_new = (const char*)K_new;
+      a.V_new = (const char*)V_new;
+      a.nsb = sb;
+      a.nsh = sh;
+      a.nst = st;
+      a.capacity = c->capacity;
+      a.n_static = c->n_static;
+      a.n_tail = c->n_tail;
+      a.n_seen = c->n_seen;
+      a.n_new = n_new;
+      a.rounds = q;
+      a.B = n.B;
+      a.H = n.H;
+      a.D = n.D;
+      a.S = n.S;
+      a.L = n.L;
+      a.k = n.k;
+      a.esize = n.esize;
+      a.ddof = n.ddof;
+      a.variant = n.variant;
+      a.nwaves = pick_waves(n);
+      e = launch_fused_append(a, s);
+    }
+  } else {
+    if (!staged_fits(n)) return LAGKV_ESHAPE;
+    const int64_t rows_staged = q > 0 ? q * n.k + (tail - q * n.L) : 0;
+    const AppendWs w = append_ws(n, q, rows_staged);
+    if (q > 0 && (!ws || ws_bytes < w.total || !aligned_to(ws, 16))) return LAGKV_EWORKSPACE;
+    const int64_t csh = c->capacity * n.rowbytes, csb = csh * n.H;
+    if (n_new > 0) {
+      e = launch_copy_rows((const char*)K_new, sb, sh, st, (char*)c->K + held * n.rowbytes, csb, csh,
+                           n.rowbytes, n.B, n.H, n_new, n.rowbytes, s);
+      if (e == hipSuccess)
+        e = launch_copy_rows((const char*)V_new, sb, sh, st, (char*)c->V + held * n.rowbytes, csb,
+                             csh, n.rowbytes, n.B, n.H, n_new, n.rowbytes, s);
+      if (e == hipSuccess && c->pos)
+        e = launch_iota_rows(c->pos, n.streams, c->capacity, held, n_new, (int32_t)c->n_seen, s);
+    }
+    if (e == hipSuccess && q > 0) {
+      char* wsb = (char*)ws;
+      float* sc = (float*)(wsb + w.off_scores);
+      int32_t* kept = (int32_t*)(wsb + w.off_kept);
+      PassArgs a;
+      lagkv_plan_t pl;
+      pl.n_chunks = q + 1;
+      pl.n_scored = q;
+      pl.rem = 0;
+      pl.k = n.k;
+      pl.T_out = rows_staged;
+      fill_pass(&a, n, c->K, c->V, total, pl, csb, csh, n.rowbytes);
+      e = launch_staged_score(a, base, sc, s);
+      if (e == hipSuccess) e = launch_select(sc, n.streams, q, n.L, n.k, base, kept, s);
+      GatherMap m;
+      m.n_pre = 0;
+      m.pre0 = 0;
+      m.n_kept = q * n.k;
+      m.post0 = base + q * n.L;
+      m.n_out = rows_staged;
+      const int64_t ssh = rows_staged * n.rowbytes, ssb = ssh * n.H;
+      if (e == hipSuccess)
+        e = launch_gather_rows((const char*)c->K, csb, csh, n.rowbytes, n.B, n.H, wsb + w.off_k,
+                               n.rowbytes, n.esize, kept, nullptr, m, s);
+      if (e == hipSuccess)
+        e = launch_gather_rows((const char*)c->V, csb, csh, n.rowbytes, n.B, n.H, wsb + w.off_v,
+                               n.rowbytes, n.esize, kept, nullptr, m, s);
+      if (e == hipSuccess)
+        e = launch_copy_rows(wsb + w.off_k, ssb, ssh, n.rowbytes, (char*)c->K + base * n.rowbytes,
+                             csb, csh, n.rowbytes, n.B, n.H, rows_staged, n.rowbytes, s);
+      if (e == hipSuccess)
+        e = launch_copy_rows(wsb + w.off_v, ssb, ssh, n.rowbytes, (char*)c->V + base * n.rowbytes,
+                             csb, csh, n.rowbytes, n.B, n.H, rows_staged, n.rowbytes, s);
+      if (e == hipSuccess && c->pos) {
+        // positions are a [streams, capacity] tensor of one 4-byte channel
+        e = launch_gather_rows((const char*)c->pos, c->capacity * 4 * n.H, c->capacity * 4, 4, n.B,
+                               n.H, wsb + w.off_pos, 4, 4, kept, nullptr, m, s);
+        if (e == hipSuccess)
+          e = launch_copy_rows(wsb + w.off_pos, rows_staged * 4 * n.H, rows_staged * 4, 4,
+                               (char*)c->pos + base * 4, c->capacity * 4 * n.H, c->capacity * 4, 4,
+                               n.B, n.H, rows_staged, 4, s);
+      }
+    }
+  }
+  if (e != hipSuccess) return LAGKV_EHIP;
+  c->n_seen += n_new;
+  c->n_static = base + q * n.k;
+  c->n_tail = tail - q * n.L;
+  return LAGKV_OK;
+}
+
+int lagkv_tune(int key, int64_t value) {
+  if (key < 0 || key >= LAGKV_TUNE_COUNT || value < 0) return LAGKV_EINVAL;
+  if (key == LAGKV_TUNE_PATH && value > 2) return LAGKV_EINVAL;
+  if (key == LAGKV_TUNE_WAVES && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+    return LAGKV_EINVAL;
+  if (key == LAGKV_TUNE_SEGMENTS && value > (1 << 20)) return LAGKV_EINVAL;
+  g_tune[key] = value;
+  return LAGKV_OK;
+}
+
+const char* lagkv_strerror(int status) {
+  switch (status) {
+    case LAGKV_OK: return "ok";
+    case LAGKV_EINVAL: return "invalid argument (null pointer, r outside (0,1], floor(r*L) < 1, S < 0, L < 1, misaligned pointer)";
+    case LAGKV_ESHAPE: return "unsupported or inconsistent shape, stride or size";
+    case LAGKV_EDTYPE: return "unknown dtype or scoring variant";
+    case LAGKV_ECAPACITY: return "cache capacity too small for the appended rows";
+    case LAGKV_EWORKSPACE: return "workspace missing, misaligned or smaller than lagkv_workspace_bytes()";
+    case LAGKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int lagkv_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,181 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, its partition arithmetic equals Eq. 12 / the oracle, and
+every validation error is returned before any device work."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import lagkv_oracle as O
+from paper_2504_04704_amd import lagkv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lagkv.lib_path()):
+        from paper_2504_04704_amd import build
+        build.build_library(verbose=False)
+    return lagkv.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "lagkv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lagkv_[a-z_]+)\s*\(", header))
+    assert declared == set(lagkv.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_header(tmp_path):
+    """The header compiles as plain C and ctypes mirrors its struct layouts."""
+    src = tmp_path / "layout.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include <stddef.h>
+#include "lagkv.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\n", sizeof(lagkv_params), offsetof(lagkv_params, r),
+         offsetof(lagkv_params, dtype), offsetof(lagkv_params, stride_b), offsetof(lagkv_params, stride_t),
+         sizeof(lagkv_plan_t), offsetof(lagkv_plan_t, T_out), sizeof(lagkv_cache),
+         offsetof(lagkv_cache, capacity), offsetof(lagkv_cache, n_seen));
+  return 0;
+}
+""")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
+    P, T, K = lagkv.Params, lagkv.PlanT, lagkv.CacheT
+    assert got == [C.sizeof(P), P.r.offset, P.dtype.offset, P.stride_b.offset, P.stride_t.offset,
+                   C.sizeof(T), T.T_out.offset, C.sizeof(K), K.capacity.offset, K.n_seen.offset]
+
+
+def test_plan_equals_eq12_and_oracle(lib):
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        S = int(rng.integers(0, 40)); L = int(rng.integers(1, 300)); k = int(rng.integers(1, L + 1))
+        T = int(rng.integers(1, 5000)); r = (k + 0.5) / L if k < L else 1.0
+        p = lagkv.make_params(1, 1, 8, S, L, r)
+        pl = lagkv.plan(p, T)
+        want = O.plan(T, S, L, r)
+        assert (pl.n_chunks, pl.n_scored, pl.rem, pl.k, pl.T_out) == \
+            (want["n_chunks"], want["n_scored"], want["rem"], want["k"], want["T_out"])
+        if T >= S + 2 * L:
+            assert pl.T_out == O.eq12_length(T, S, L, k)
+    for T, S, L, rL, n_s, LR in [(1024, 16, 128, 64, 6, 640), (16384, 16, 128, 32, 126, 4288),
+                                 (65536, 16, 256, 32, 254, 8640), (131072, 16, 512, 128, 254, 33536),
+                                 (32768, 16, 128, 32, 254, 8384), (40960, 16, 128, 32, 318, 10432)]:
+        pl = lagkv.plan(lagkv.make_params(4, 8, 128, S, L, rL / L), T)
+        assert (pl.k, pl.n_scored, pl.T_out) == (rL, n_s, LR)
+    # explicit static part (second pass over a compressed cache is a no-op)
+    pl = lagkv.plan(lagkv.make_params(1, 1, 8, 16, 128, 0.25), 4288, 16 + 126 * 32)
+    assert pl.n_scored == 0 and pl.T_out == 4288
+
+
+def _status(fn, *a):
+    try:
+        fn(*a)
+    except lagkv.LagKVError as e:
+        return e.status
+    return lagkv.OK
+
+
+def test_parameter_validation(lib):
+    ok = dict(B=1, H=2, D=64, S=16, L=128, r=0.5)
+    def P(**kw):
+        d = dict(ok); d.update(kw)
+        extra = {k: d.pop(k) for k in ("dtype", "variant", "std_ddof", "strides") if k in d}
+        return lagkv.make_params(d["B"], d["H"], d["D"], d["S"], d["L"], d["r"], **extra)
+    assert _status(lagkv.plan, P(), 1024) == lagkv.OK
+    assert _status(lagkv.plan, P(r=0.0), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(r=1.5), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(r=float("nan")), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(r=0.001), 1024) == lagkv.EINVAL          # floor(r*L) < 1
+    assert _status(lagkv.plan, P(L=0), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(S=-1), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(D=1), 1024) == lagkv.ESHAPE              # ddof=1 needs D>=2
+    assert _status(lagkv.plan, P(D=1, std_ddof=0), 1024) == lagkv.OK
+    assert _status(lagkv.plan, P(std_ddof=2), 1024) == lagkv.EINVAL
+    assert _status(lagkv.plan, P(B=0), 1024) == lagkv.ESHAPE
+    assert _status(lagkv.plan, P(dtype=7), 1024) == lagkv.EDTYPE
+    assert _status(lagkv.plan, P(variant=3), 1024) == lagkv.EDTYPE
+    assert _status(lagkv.plan, P(strides=(-1, 0, 0)), 1024) == lagkv.ESHAPE
+    assert _status(lagkv.plan, P(), -5) == lagkv.ESHAPE
+    assert lib.lagkv_plan(None, 10, -1, C.byref(lagkv.PlanT())) == lagkv.EINVAL
+    assert lib.lagkv_plan(C.byref(P()), 10, -1, None) == lagkv.EINVAL
+    p = P(); p.reserved = 1
+    assert _status(lagkv.plan, p, 1024) == lagkv.EINVAL
+
+
+def test_calls_reject_bad_arguments_before_touching_the_device(lib):
+    p = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32)
+    fake = 0x1000                      # never dereferenced: validation fails first
+    assert lib.lagkv_score(C.byref(p), None, fake, 1024, fake, None, 0, None) == lagkv.EINVAL
+    assert lib.lagkv_score(C.byref(p), fake, fake, 1024, None, None, 0, None) == lagkv.EINVAL
+    assert lib.lagkv_score(C.byref(p), fake + 2, fake, 1024, fake, None, 0, None) == lagkv.EINVAL
+    assert lib.lagkv_score(C.byref(p), fake, fake, 0, fake, None, 0, None) == lagkv.ESHAPE
+    assert lib.lagkv_score(C.byref(p), fake, fake, 100, None, None, 0, None) == lagkv.OK  # below 2L: no-op
+    assert lib.lagkv_select(C.byref(p), None, 1024, fake, None) == lagkv.EINVAL
+    assert lib.lagkv_select(C.byref(p), fake, 100, None, None) == lagkv.OK
+    assert lib.lagkv_compress(C.byref(p), fake, fake, 1024, None, fake, None, None, None, 0, None) == lagkv.EINVAL
+    bad_stride = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32, strides=(0, 0, 32))
+    assert lib.lagkv_compress(C.byref(bad_stride), fake, fake, 1024, fake, fake, None, None, None, 0,
+                              None) == lagkv.ESHAPE
+    # a shape only the three-kernel path serves needs a workspace
+    odd = lagkv.make_params(1, 2, 40, 16, 128, 0.5, lagkv.F32)
+    need = lagkv.workspace_bytes(odd, 1024)
+    assert need > 0 and lagkv.workspace_bytes(p, 1024) == 0
+    assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, None, 0,
+                              None) == lagkv.EWORKSPACE
+    assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, fake, 64,
+                              None) == lagkv.EWORKSPACE
+    # forcing the fused kernels on a shape they do not cover is an error, not a fallback
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
+    try:
+        assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, fake, need,
+                                  None) == lagkv.ESHAPE
+    finally:
+        lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
+    # L beyond what fits the per-workgroup LDS budget
+    huge = lagkv.make_params(1, 1, 64, 0, 1 << 20, 0.5, lagkv.F32)
+    assert lib.lagkv_score(C.byref(huge), fake, fake, 1 << 22, fake, None, 0, None) == lagkv.ESHAPE
+
+
+def test_append_validation(lib):
+    p = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32)
+    fake = 0x1000
+    c = lagkv.CacheT(fake, fake, None, 512, 16, 200, 216)
+    assert lib.lagkv_append_and_compress(C.byref(p), C.byref(c), fake, fake, 400, None, 0, None) \
+        == lagkv.ECAPACITY
+    assert (c.n_static, c.n_tail, c.n_seen) == (16, 200, 216)          # untouched on error
+    assert lib.lagkv_append_and_compress(C.byref(p), C.byref(c), None, fake, 4, None, 0, None) == lagkv.EINVAL
+    assert lib.lagkv_append_and_compress(C.byref(p), None, fake, fake, 4, None, 0, None) == lagkv.EINVAL
+    assert lib.lagkv_append_and_compress(C.byref(p), C.byref(c), fake, fake, -1, None, 0, None) == lagkv.EINVAL
+    c2 = lagkv.CacheT(None, fake, None, 512, 0, 0, 0)
+    assert lib.lagkv_append_and_compress(C.byref(p), C.byref(c2), fake, fake, 4, None, 0, None) == lagkv.EINVAL
+
+
+def test_tune_and_strerror(lib):
+    assert _status(lagkv.tune, 99, 1) == lagkv.EINVAL
+    assert _status(lagkv.tune, lagkv.TUNE_WAVES, 3) == lagkv.EINVAL
+    assert _status(lagkv.tune, lagkv.TUNE_PATH, 5) == lagkv.EINVAL
+    lagkv.tune(lagkv.TUNE_WAVES, 8); lagkv.tune(lagkv.TUNE_WAVES, 0)
+    for s in range(7):
+        assert len(lagkv.strerror(s)) > 1
+    assert lagkv.strerror(1234) == "unknown status"
+    assert lagkv.version() >= 100
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    K = torch.zeros(1, 1, 512, 64)
+    with pytest.raises(RuntimeError):
+        lagkv.compress(K, K.clone(), 16, 128, 0.5)
+    with pytest.raises(RuntimeError):
+        lagkv.score(K, K.clone(), 16, 128, 0.5)

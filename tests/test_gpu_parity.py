@@ -1,0 +1,329 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs (element by element at small sizes; sampled streams plus size-free
+invariants at the full workload sizes)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lagkv_oracle as O
+from paper_2504_04704_amd import lagkv, synth
+from tests import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+VARIANT_NAME = {lagkv.SCORE_LAG: "lag", lagkv.SCORE_LOCAL: "local", lagkv.SCORE_L2: "l2"}
+
+
+def say(*a):
+    print("[gpu-test]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning():
+    lagkv.load()
+    yield
+    for key in (lagkv.TUNE_PATH, lagkv.TUNE_WAVES, lagkv.TUNE_SEGMENTS):
+        lagkv.tune(key, 0)
+
+
+def gen(B, H, T, D, dtype, seed, device=DEV):
+    cfg = synth.KVConfig("t", layers=1, B=B, H=H, D=D, T=T, S=0, L=1, r=1.0,
+                         dtype="f32" if dtype == torch.float32 else "bf16", n_outlier=min(2, D // 8))
+    return synth.make_kv(cfg, device=device, seed=seed)
+
+
+def run_and_check(K, V, S, L, r, variant=lagkv.SCORE_LAG, ddof=1, streams=None):
+    out = lagkv.compress(K, V, S, L, r, variant=variant, std_ddof=ddof, want_scores=True)
+    torch.cuda.synchronize()
+    B, H, T, D = K.shape
+    rep = PU.StreamReport()
+    todo = streams if streams is not None else [(b, h) for b in range(B) for h in range(H)]
+    for b, h in todo:
+        sc = out.scores[b, h] if out.scores is not None and out.scores.numel() else None
+        rep.merge(PU.check_stream(K[b, h], V[b, h], S, L, r, out.idx[b, h], out.K[b, h], out.V[b, h],
+                                  sc, ddof, VARIANT_NAME[variant]))
+    return out, rep
+
+
+# ---------------------------------------------------------------- one-shot pass
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+def test_config1_tiny_fp32(path):
+    cfg = synth.CONFIGS["cfg1_tiny_f32"]
+    say("config 1", cfg, "path", path)
+    K, V = synth.make_kv(cfg, device=DEV)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    out, rep = run_and_check(K, V, cfg.S, cfg.L, cfg.r)
+    assert out.plan.T_out == 640 and rep.chunks == 12
+    say("config 1 ok: flipped", rep.flipped_chunks, "max score rel", rep.max_score_rel)
+
+
+SHAPES = [
+    # B, H, T, D, dtype, S, L, r
+    (2, 2, 16 + 5 * 128 + 37, 128, torch.bfloat16, 16, 128, 0.25),
+    (1, 3, 4 + 6 * 100 + 99, 128, torch.bfloat16, 4, 100, 0.33),     # ragged L, odd k
+    (1, 2, 7 * 24, 64, torch.float32, 0, 24, 0.5),                   # S = 0, no remainder
+    (2, 1, 16 + 3 * 512 + 11, 128, torch.bfloat16, 16, 512, 0.25),
+    (1, 2, 9 + 4 * 257, 64, torch.bfloat16, 9, 257, 0.125),          # LPR = 8
+    (1, 2, 5 + 5 * 64 + 3, 256, torch.bfloat16, 5, 64, 0.5),         # LPR = 32
+    (1, 2, 5 + 5 * 70 + 3, 32, torch.bfloat16, 5, 70, 0.1),          # LPR = 4
+    (1, 2, 3 + 4 * 130, 128, torch.float32, 3, 130, 0.3),            # fp32, LPR = 32
+    (1, 1, 16 + 2 * 1024 + 5, 128, torch.bfloat16, 16, 1024, 0.125),
+    (1, 1, 2 + 2 * 1500 + 1, 64, torch.float32, 2, 1500, 0.01),      # L > 1024: LDS-resident keys
+    (3, 2, 1 + 9 * 3, 16, torch.float32, 1, 3, 0.67),                # tiny L
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}T{s[2]}D{s[3]}{'f32' if s[4] == torch.float32 else 'bf16'}S{s[5]}L{s[6]}")
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+def test_shapes_against_oracle(shape, path):
+    B, H, T, D, dtype, S, L, r = shape
+    say("shape", shape, "path", path)
+    K, V = gen(B, H, T, D, dtype, seed=hash(shape[:4]) & 0xffff)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    out, rep = run_and_check(K, V, S, L, r)
+    assert out.plan.T_out == O.plan(T, S, L, r)["T_out"]
+    say("ok: chunks", rep.chunks, "flipped", rep.flipped_chunks, "max rel", rep.max_score_rel)
+
+
+@pytest.mark.parametrize("D,dtype", [(40, torch.float32), (96, torch.bfloat16), (5, torch.float32), (300, torch.bfloat16)])
+def test_unaligned_head_dims_use_the_staged_path(D, dtype):
+    say("unaligned D", D, dtype)
+    K, V = gen(1, 2, 8 + 4 * 50 + 7, D, dtype, seed=D)
+    assert lagkv.workspace_bytes(lagkv.params_for(K, 8, 50, 0.3), K.shape[2]) > 0
+    run_and_check(K, V, 8, 50, 0.3)
+
+
+@pytest.mark.parametrize("nw", [1, 2, 4, 8])
+@pytest.mark.parametrize("nseg", [1, 3, 1000])
+def test_launch_shapes_agree(nw, nseg):
+    say("launch shape nw", nw, "nseg", nseg)
+    K, V = gen(2, 2, 16 + 9 * 96 + 50, 128, torch.bfloat16, seed=5)
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
+    lagkv.tune(lagkv.TUNE_WAVES, nw)
+    lagkv.tune(lagkv.TUNE_SEGMENTS, nseg)
+    run_and_check(K, V, 16, 96, 0.25)
+
+
+def test_strided_input_views():
+    say("strided views")
+    B, H, T, D = 2, 3, 16 + 4 * 64 + 9, 128
+    base_k = torch.empty(B, T, H, 2 * D, dtype=torch.bfloat16, device=DEV)      # [B,T,H,2D] storage
+    base_v = torch.empty_like(base_k)
+    K0, V0 = gen(B, H, T, D, torch.bfloat16, seed=11)
+    K = base_k[..., :D].permute(0, 2, 1, 3); V = base_v[..., :D].permute(0, 2, 1, 3)
+    K.copy_(K0); V.copy_(V0)
+    assert not K.is_contiguous() and K.stride(3) == 1
+    out, _ = run_and_check(K, V, 16, 64, 0.25)
+    ref = lagkv.compress(K0, V0, 16, 64, 0.25)
+    torch.cuda.synchronize()
+    assert torch.equal(out.idx, ref.idx) and torch.equal(out.K, ref.K) and torch.equal(out.V, ref.V)
+
+
+def test_noop_below_two_lags_and_identity_at_r1():
+    say("no-op / identity")
+    K, V = gen(1, 2, 16 + 2 * 128 - 1, 128, torch.bfloat16, seed=3)
+    out = lagkv.compress(K, V, 16, 128, 0.25, want_scores=True)
+    torch.cuda.synchronize()
+    assert out.plan.n_scored == 0 and torch.equal(out.K, K) and torch.equal(out.V, V)
+    assert torch.equal(out.idx[0, 0].cpu(), torch.arange(K.shape[2], dtype=torch.int32))
+    assert lagkv.score(K, V, 16, 128, 0.25).numel() == 0
+    K, V = gen(1, 2, 16 + 4 * 32 + 5, 128, torch.bfloat16, seed=4)
+    for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
+        lagkv.tune(lagkv.TUNE_PATH, path)
+        out = lagkv.compress(K, V, 16, 32, 1.0)
+        torch.cuda.synchronize()
+        assert torch.equal(out.K, K) and torch.equal(out.V, V)
+
+
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+def test_degenerate_channel_and_duplicate_tokens(path):
+    say("degenerate channel / duplicates, path", path)
+    K, V = gen(1, 2, 8 + 4 * 64, 128, torch.bfloat16, seed=21)
+    K[:, :, 8 + 64:8 + 128, 5] = 1.25          # constant channel in the reference of chunk 0
+    V[:, :, :, 17] = -3.0                      # constant in every reference
+    K[0, 0, 8 + 10] = K[0, 0, 8 + 3]; V[0, 0, 8 + 10] = V[0, 0, 8 + 3]   # exact duplicates -> exact tie
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    out, rep = run_and_check(K, V, 8, 64, 0.5)
+    sc = out.scores[0, 0].cpu()
+    assert torch.isfinite(out.scores).all()
+    assert sc[3] == sc[10]
+
+
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 48)])
+def test_scoring_variants(variant, dtype, D):
+    say("variant", variant, dtype, D)
+    K, V = gen(1, 2, 16 + 5 * 64 + 3, D, dtype, seed=31 + variant)
+    run_and_check(K, V, 16, 64, 0.25, variant=variant)
+
+
+def test_ddof_zero():
+    K, V = gen(1, 2, 16 + 3 * 64, 128, torch.bfloat16, seed=41)
+    for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
+        lagkv.tune(lagkv.TUNE_PATH, path)
+        run_and_check(K, V, 16, 64, 0.25, ddof=0)
+
+
+# ------------------------------------------------------- stage-by-stage entry points
+def test_score_entry_point_matches_oracle():
+    say("lagkv_score")
+    K, V = gen(2, 2, 16 + 4 * 128 + 9, 128, torch.bfloat16, seed=51)
+    for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
+        lagkv.tune(lagkv.TUNE_PATH, path)
+        sc = lagkv.score(K, V, 16, 128, 0.25)
+        torch.cuda.synchronize()
+        for b in range(2):
+            for h in range(2):
+                want = O.score(PU.to_f64(K[b, h]), PU.to_f64(V[b, h]), 16, 128)
+                PU.check_scores(sc[b, h].cpu().numpy(), want)
+        assert torch.allclose(sc.view(2, 2, 4, 128).sum(-1), torch.full((2, 2, 4), 2.0, device=DEV), atol=1e-5)
+
+
+@pytest.mark.parametrize("L,k", [(128, 32), (100, 33), (512, 128), (64, 64), (1500, 7), (3, 1), (70, 69)])
+def test_select_entry_point_is_exact_with_ties(L, k):
+    say("lagkv_select", L, k)
+    g = torch.Generator(device="cpu"); g.manual_seed(L * 1000 + k)
+    B, H, n_s, S = 2, 2, 5, 4
+    T = S + (n_s + 1) * L + 1
+    sc = torch.randn(B, H, n_s * L, generator=g)
+    sc[0] = torch.round(sc[0] * 4) / 4                      # many exact ties, negative values, zeros
+    sc[1, 0, :L] = 0.5                                      # a whole chunk tied
+    sc[1, 1, 0] = -0.0; sc[1, 1, 1] = 0.0
+    kept = lagkv.select(sc.to(DEV), T, S, L, (k + 0.5) / L if k < L else 1.0)
+    torch.cuda.synchronize()
+    assert kept.shape == (B, H, n_s, k)
+    kept = kept.cpu().numpy()
+    s64 = sc.numpy().astype(np.float64)
+    for b in range(B):
+        for h in range(H):
+            want = O.select(s64[b, h], L, k, S)
+            assert np.array_equal(kept[b, h], want)
+
+
+# -------------------------------------------------------------- decode-time variant
+def oracle_history_check(cache, Kh, Vh, S, L, r, variant="lag"):
+    gK, gV, gpos = cache.view()
+    B, H = gK.shape[:2]
+    flipped = 0
+    for b in range(B):
+        for h in range(H):
+            rep = PU.check_stream(Kh[b, h], Vh[b, h], S, L, r, gpos[b, h], gK[b, h], gV[b, h], None, 1, variant)
+            flipped += rep.flipped_chunks
+    pl = O.plan(Kh.shape[2], S, L, r)
+    assert cache.length == pl["T_out"] and cache.n_seen == Kh.shape[2]
+    if pl["n_scored"]:
+        assert cache.n_static == S + pl["k"] * pl["n_scored"] and cache.n_tail == L + pl["rem"]
+    return flipped
+
+
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+@pytest.mark.parametrize("steps", [[1] * 150, [7, 64, 1, 200, 3, 3, 130], [400], [16, 127, 1, 128, 128]])
+def test_append_from_empty_equals_one_shot(path, steps):
+    say("append from empty", steps[:6], "path", path)
+    S, L, r, D = 6, 32, 0.25, 128
+    T = sum(steps)
+    Kh, Vh = gen(1, 2, T, D, torch.bfloat16, seed=61)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    cache = lagkv.Cache(1, 2, D, T + 8, S, L, r)
+    t = 0
+    for n in steps:
+        cache.append_and_compress(Kh[:, :, t:t + n], Vh[:, :, t:t + n])
+        t += n
+        assert cache.n_tail < 2 * L or cache.n_seen < S + 2 * L
+    torch.cuda.synchronize()
+    oracle_history_check(cache, Kh, Vh, S, L, r)
+
+
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+@pytest.mark.parametrize("dtype,D,variant", [(torch.bfloat16, 128, lagkv.SCORE_LAG), (torch.float32, 64, lagkv.SCORE_LAG),
+                                             (torch.bfloat16, 128, lagkv.SCORE_LOCAL), (torch.float32, 40, lagkv.SCORE_L2)])
+def test_append_after_one_shot_equals_one_shot_on_history(path, dtype, D, variant):
+    if path == lagkv.PATH_FUSED and (D == 40 or variant == lagkv.SCORE_L2):
+        pytest.skip("shape/variant served by the three-kernel path only")
+    say("append after compress", dtype, D, variant, "path", path)
+    S, L, r = 16, 64, 0.25
+    T0, rounds = 16 + 6 * 64 + 20, 5
+    Kh, Vh = gen(2, 2, T0 + rounds * L, D, dtype, seed=71)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    comp = lagkv.compress(Kh[:, :, :T0].contiguous(), Vh[:, :, :T0].contiguous(), S, L, r, variant=variant)
+    cache = lagkv.Cache.from_compressed(comp, T0, comp.plan.T_out + 3 * L, S, L, r, variant=variant)
+    for i in range(rounds):
+        a = T0 + i * L
+        cache.append_and_compress(Kh[:, :, a:a + L], Vh[:, :, a:a + L])     # strided views of the history
+    cache.append_and_compress(None, None)                                   # n_new = 0 is allowed
+    torch.cuda.synchronize()
+    oracle_history_check(cache, Kh, Vh, S, L, r, VARIANT_NAME[variant])
+
+
+def test_append_capacity_error_leaves_cache_untouched():
+    cache = lagkv.Cache(1, 1, 128, 64, 4, 16, 0.5)
+    Kn, Vn = gen(1, 1, 65, 128, torch.bfloat16, seed=81)
+    with pytest.raises(lagkv.LagKVError) as e:
+        cache.append_and_compress(Kn, Vn)
+    assert e.value.status == lagkv.ECAPACITY and cache.length == 0 and cache.n_seen == 0
+
+
+# ------------------------------------------------------------ full workload sizes
+def _full_config(name, n_sample, want_scores=True):
+    cfg = synth.CONFIGS[name]
+    say("full config", name, "streams", cfg.streams, "T", cfg.T)
+    K, V = synth.make_kv(cfg, device=DEV)
+    out = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, want_scores=want_scores)
+    torch.cuda.synchronize()
+    pl = out.plan
+    PU.check_index_invariants(out.idx, cfg.T, cfg.S, cfg.L, pl.k, pl.n_scored)
+    rep = PU.StreamReport()
+    for s in synth.stream_sample(cfg.streams, n_sample):
+        b, h = divmod(s, cfg.H)
+        sc = out.scores[b, h] if want_scores else None
+        rep.merge(PU.check_stream(K[b, h], V[b, h], cfg.S, cfg.L, cfg.r, out.idx[b, h], out.K[b, h],
+                                  out.V[b, h], sc))
+    say(name, "ok: sampled chunks", rep.chunks, "near-tie flips", rep.flipped_chunks,
+        "max score rel err", f"{rep.max_score_rel:.2e}")
+    return out, rep
+
+
+def test_config2_llama8b_16k():
+    out, _ = _full_config("cfg2_llama8b_16k", 24)
+    assert out.plan.T_out == 4288
+
+
+def test_config3_llama8b_64k():
+    out, _ = _full_config("cfg3_llama8b_64k", 8)
+    assert out.plan.T_out == 8640
+
+
+def test_config4_llama8b_128k_b4_bench_configuration():
+    """The headline workload in the launch configuration bench.py times (defaults,
+    no score dump): 64 GiB scanned, sampled streams against the oracle."""
+    out, _ = _full_config("cfg4_llama8b_128k_b4", 6, want_scores=False)
+    assert out.plan.T_out == 33536
+
+
+def test_config5_decode_rounds_reduced_batch():
+    """Config 5 at reduced batch (B=1 instead of 32: 256 streams) and 6 of the 64 rounds;
+    bench.py times the full batch.  Final caches of sampled streams against the one-shot
+    oracle on the concatenated history."""
+    cfg = synth.CONFIGS["cfg5_decode_b32"].scaled(B=1)
+    say("config 5 (B=1)", cfg)
+    K, V = synth.make_kv(cfg, device=DEV)
+    comp = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r)
+    assert comp.plan.T_out == 8384
+    rounds = 6
+    cache = lagkv.Cache.from_compressed(comp, cfg.T, comp.plan.T_out + rounds * 32 + cfg.L, cfg.S, cfg.L, cfg.r)
+    hist_k, hist_v = [K], [V]
+    for i in range(rounds):
+        Kn, Vn = synth.make_new_tokens(cfg, cfg.L, i, device=DEV)
+        cache.append_and_compress(Kn, Vn)
+        hist_k.append(Kn); hist_v.append(Vn)
+        assert cache.n_tail == 240 and cache.length == 8384 + 32 * (i + 1)
+    torch.cuda.synchronize()
+    Kh, Vh = torch.cat(hist_k, dim=2), torch.cat(hist_v, dim=2)
+    gK, gV, gpos = cache.view()
+    PU.check_index_invariants(gpos, Kh.shape[2], cfg.S, cfg.L, 32, 254 + rounds)
+    for s in synth.stream_sample(cfg.streams, 6):
+        b, h = divmod(s, cfg.H)
+        PU.check_stream(Kh[b, h], Vh[b, h], cfg.S, cfg.L, cfg.r, gpos[b, h], gK[b, h], gV[b, h])
