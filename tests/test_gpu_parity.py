@@ -179,7 +179,7 @@ def test_score_entry_point_matches_oracle():
             for h in range(2):
                 want = O.score(PU.to_f64(K[b, h]), PU.to_f64(V[b, h]), 16, 128)
                 PU.check_scores(sc[b, h].cpu().numpy(), want)
-        assert torch.allclose(sc.view(2, 2, 4, 128).sum(-1), torch.full((2, 2, 4), 2.0, device=DEV), atol=1e-5)
+        assert torch.allclose(sc.view(2, 2, 3, 128).sum(-1), torch.full((2, 2, 3), 2.0, device=DEV), atol=1e-5)
 
 
 @pytest.mark.parametrize("L,k", [(128, 32), (100, 33), (512, 128), (64, 64), (1500, 7), (3, 1), (70, 69)])
