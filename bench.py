@@ -219,12 +219,44 @@ def bench_decode(args):
     }
 
 
+def bench_copy(args):
+    """Calibration workload for the HBM counters: the library's plain row-copy kernel
+    (the no-op branch of lagkv_compress, taken when T - S < 2L) on tensors of known
+    size: every launch of copy_rows_kernel reads 1 GiB and writes 1 GiB."""
+    import torch
+    from paper_2504_04704_amd import lagkv
+
+    dev = "cuda:0"
+    lagkv.load()
+    K = torch.randn((64, 8, 8192, 128), device=dev).to(torch.bfloat16)
+    V = torch.randn((64, 8, 8192, 128), device=dev).to(torch.bfloat16)
+    Ko, Vo = torch.empty_like(K), torch.empty_like(V)
+    nbytes = K.numel() * 2
+    evs = []
+    for i in range(args.steps + args.warmup):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        lagkv.compress(K, V, 16, 8192, 0.25, out=(Ko, Vo), want_idx=False)
+        e.record()
+        evs.append((s, e))
+    torch.cuda.synchronize()
+    ms = [s.elapsed_time(e) for s, e in evs[args.warmup:]]
+    avg = sum(ms) / len(ms)
+    assert torch.equal(Ko, K) and torch.equal(Vo, V)
+    return {"metric": "copy_rows_calibration", "value": 4 * nbytes / (avg * 1e-3) / 1e9, "unit": "GB/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": avg,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+            "data": "synthetic",
+            "config": {"workload": "copy_rows 2 launches x (1 GiB read + 1 GiB written)",
+                       "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["compress", "decode"], default="compress")
+    ap.add_argument("--workload", choices=["compress", "decode", "copy"], default="compress")
     ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--cpu-streams", type=int, default=32)
@@ -240,7 +272,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
-    res = bench_compress(args) if args.workload == "compress" else bench_decode(args)
+    res = {"compress": bench_compress, "decode": bench_decode, "copy": bench_copy}[args.workload](args)
     print(json.dumps(res), flush=True)
 
 
