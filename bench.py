@@ -129,7 +129,7 @@ def bench_compress(args):
     tokens = cfg.B * cfg.T                      # one token = one (batch, position) over all layers and heads
     alg = algorithmic_bytes(cfg.streams, cfg.T, pl.T_out, cfg.D, K.element_size())
     achieved = alg / (kern_avg_ms * 1e-3) / 1e9
-    traffic = read_traffic(f"fused_pass_{cfg.name}_traffic.txt")
+    traffic = read_traffic(f"split_pass_{cfg.name}_traffic.txt")
     res = {
         "metric": "kv_tokens_compressed_per_sec_128k_ctx" if cfg.T == 131072 else "kv_tokens_compressed_per_sec",
         "value": tokens / (ms_per_step * 1e-3),
@@ -144,7 +144,7 @@ def bench_compress(args):
                    "head_tokens_per_s": cfg.streams * cfg.T / (ms_per_step * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "fused_pass_kernel", "kernel_ms_avg": kern_avg_ms,
+                     "kernel": "split_pass_kernel", "kernel_ms_avg": kern_avg_ms,
                      "kernel_ms_min": min(kern_ms), "algorithmic_bytes": alg},
     }
     if not args.no_cpu:

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblagkv.so")
-SOURCES = ["lagkv_api.hip", "fused_pass.hip", "staged_pass.hip"]
+SOURCES = ["lagkv_api.hip", "fused_pass.hip", "resident_pass.hip", "split_pass.hip", "staged_pass.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,10 +27,10 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
+def build_library(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH) -> str:
     """Compile every HIP source into paper_2504_04704_amd/liblagkv.so; returns its path."""
     cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH + ".tmp"]
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out_path + ".tmp"]
     if verbose:
         print("[build]", " ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -41,8 +41,8 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
         print(out, flush=True)
     if proc.returncode != 0:
         raise RuntimeError(f"hipcc failed ({proc.returncode})\n{out}")
-    os.replace(LIB_PATH + ".tmp", LIB_PATH)
-    return LIB_PATH
+    os.replace(out_path + ".tmp", out_path)
+    return out_path
 
 
 if __name__ == "__main__":

@@ -13,42 +13,10 @@
 // wavefront runs the chunk softmax (Eq. 10-11) and the top-k; then all wavefronts
 // copy the kept rows (a re-read that is served by the caches) to the dense output.
 #include "lagkv_internal.hpp"
+#include "row_ops.hpp"
 #include "wave_ops.hpp"
 
 namespace lagkv {
-
-struct F32 {
-  static constexpr int VEC = 4;
-};
-struct BF16 {
-  static constexpr int VEC = 8;
-};
-
-template <typename ET>
-__device__ __forceinline__ void unpack(const uint4& q, float (&x)[ET::VEC]) {
-  if constexpr (ET::VEC == 4) {
-    x[0] = __uint_as_float(q.x);
-    x[1] = __uint_as_float(q.y);
-    x[2] = __uint_as_float(q.z);
-    x[3] = __uint_as_float(q.w);
-  } else {  // bf16 -> fp32 is a 16-bit shift; element 2i is the low half of word i
-    x[0] = __uint_as_float(q.x << 16);
-    x[1] = __uint_as_float(q.x & 0xffff0000u);
-    x[2] = __uint_as_float(q.y << 16);
-    x[3] = __uint_as_float(q.y & 0xffff0000u);
-    x[4] = __uint_as_float(q.z << 16);
-    x[5] = __uint_as_float(q.z & 0xffff0000u);
-    x[6] = __uint_as_float(q.w << 16);
-    x[7] = __uint_as_float(q.w & 0xffff0000u);
-  }
-}
-
-__device__ __forceinline__ uint4 ld16(const char* p) {
-  return *reinterpret_cast<const uint4*>(p);
-}
-__device__ __forceinline__ void st16(char* p, const uint4& v) {
-  *reinterpret_cast<uint4*>(p) = v;
-}
 
 // Running per-channel min/max of the lane's VEC channels (Eq. 7-8), K and V.
 template <int VEC>
@@ -87,29 +55,6 @@ struct RefStats {
   }
 };
 
-// Standard deviation over the D channels of one normalised token (Eq. 9-10).
-// Two passes: the mean first (any error in it only enters the variance to second
-// order, so the cheap fma form is used), then the centred sum of squares from the
-// exactly subtracted (x - mn).
-template <int LPR, int VEC>
-__device__ __forceinline__ float token_spread(const float (&x)[VEC], const float (&mn)[VEC],
-                                              const float (&iv)[VEC], float bias, float inv_D,
-                                              float inv_dof) {
-  float s = bias;
-#pragma unroll
-  for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
-  s = group_sum<LPR>(s);
-  const float mean = s * inv_D;
-  float ss = 0.f;
-#pragma unroll
-  for (int j = 0; j < VEC; ++j) {
-    const float d = fmaf(x[j] - mn[j], iv[j], -mean);
-    ss = fmaf(d, d, ss);
-  }
-  ss = group_sum<LPR>(ss);
-  return sqrtf(ss * inv_dof);
-}
-
 struct Geometry {
   int lane, wave, nw;  // lane in wave, wave in workgroup, waves per workgroup
   int rl, cl;          // row within a wave step, 16-byte column slice
@@ -131,7 +76,7 @@ __device__ __forceinline__ Geometry make_geometry() {
 }
 
 // One pass over the L rows of a chunk.  STATS: fold the rows into `acc`.  SCORE:
-// write the spread of every token, normalised with `ref`, to sK/sV (LDS).
+// write the channel variance of every token, normalised with `ref`, to sK/sV (LDS).
 // Rows past L are clamped to the last row (duplicates do not change min/max).
 template <typename ET, int LPR, bool STATS, bool SCORE>
 __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const char* __restrict__ vp,
@@ -166,8 +111,8 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
         }
       }
       if constexpr (SCORE) {
-        sgK0 = token_spread<LPR, VEC>(x0, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
-        sgK1 = token_spread<LPR, VEC>(x1, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
+        sgK0 = token_var<LPR, VEC>(x0, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
+        sgK1 = token_var<LPR, VEC>(x1, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
       }
       unpack<ET>(vq[u], x0);
       unpack<ET>(vq[u + 1], x1);
@@ -179,8 +124,8 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
         }
       }
       if constexpr (SCORE) {
-        sgV0 = token_spread<LPR, VEC>(x0, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
-        sgV1 = token_spread<LPR, VEC>(x1, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
+        sgV0 = token_var<LPR, VEC>(x0, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
+        sgV1 = token_var<LPR, VEC>(x1, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
         if (g.cl == 0) {
           if (r[u] < L) {
             sK[r[u]] = sgK0;
@@ -237,22 +182,6 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
     }
   } else {
     __syncthreads();
-  }
-}
-
-// dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane.
-template <int LPR>
-__device__ __forceinline__ void copy_rows_kv(const char* __restrict__ ks, const char* __restrict__ vs,
-                                             int64_t sst, char* __restrict__ kd,
-                                             char* __restrict__ vd, int64_t dst_st, int64_t nrows,
-                                             int tid, int nthreads) {
-  const int cl = tid % LPR;
-  const int64_t ng = nthreads / LPR;
-  for (int64_t r = tid / LPR; r < nrows; r += ng) {
-    const uint4 a = ld16(ks + r * sst + cl * 16);
-    const uint4 b = ld16(vs + r * sst + cl * 16);
-    st16(kd + r * dst_st + cl * 16, a);
-    st16(vd + r * dst_st + cl * 16, b);
   }
 }
 
@@ -345,10 +274,8 @@ __global__ void __launch_bounds__(512) fused_pass_kernel(const PassArgs a) {
       fold_stats<LPR, VEC>(acc, g, statbuf, a.D);  // barrier inside: spreads are visible
       ref.from(acc);                               // chunk p is the reference of chunk p-1
     }
-    if (g.wave == 0) {
-      wave_chunk_softmax(sK, sV, L, sout ? sout + p * L : nullptr, g.lane);
-      if (gather) wave_select_any(sK, L, k, list, g.lane);
-    }
+    if (g.wave == 0)
+      wave_score_select_any(sK, sV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, g.lane);
     __syncthreads();
     if (gather) {
       const char* ksrc = kin + c;
@@ -482,10 +409,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
     scan_chunk<ET, LPR, false, true>(kc + cur * rowbytes, vc + cur * rowbytes, rowbytes, L, g, acc,
                                      ref, inv_D, inv_dof, sK, sV);
     __syncthreads();
-    if (g.wave == 0) {
-      wave_chunk_softmax(sK, sV, L, nullptr, g.lane);
-      wave_select_any(sK, L, k, list, g.lane);
-    }
+    if (g.wave == 0) wave_score_select_any(sK, sV, L, k, true, nullptr, list, nullptr, g.lane);
     __syncthreads();
     // staged in-place gather of the kept rows
     constexpr int UB = 4;
@@ -526,17 +450,6 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
 // host side
 // ---------------------------------------------------------------------------------
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
-static int lanes_per_row(int D, int esize) {
-  const int64_t rb = (int64_t)D * esize;
-  switch (rb) {
-    case 64: return 4;
-    case 128: return 8;
-    case 256: return 16;
-    case 512: return 32;
-    default: return 0;
-  }
-}
 
 bool fused_supported(int D, int esize, int64_t sb, int64_t sh, int64_t st, const void* K,
                      const void* V, const void* Ko, const void* Vo) {

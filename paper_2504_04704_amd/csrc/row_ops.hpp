@@ -1,0 +1,121 @@
+// Per-row arithmetic shared by the fused LagKV kernels: element unpacking, 16-byte
+// accesses and the two-pass channel variance of a normalised token (Eq. 9-10).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wave_ops.hpp"
+
+namespace lagkv {
+
+struct F32 {
+  static constexpr int VEC = 4;
+};
+struct BF16 {
+  static constexpr int VEC = 8;
+};
+
+template <typename ET>
+__device__ __forceinline__ void unpack(const uint4& q, float (&x)[ET::VEC]) {
+  if constexpr (ET::VEC == 4) {
+    x[0] = __uint_as_float(q.x);
+    x[1] = __uint_as_float(q.y);
+    x[2] = __uint_as_float(q.z);
+    x[3] = __uint_as_float(q.w);
+  } else {  // bf16 -> fp32 is a 16-bit shift; element 2i is the low half of word i
+    x[0] = __uint_as_float(q.x << 16);
+    x[1] = __uint_as_float(q.x & 0xffff0000u);
+    x[2] = __uint_as_float(q.y << 16);
+    x[3] = __uint_as_float(q.y & 0xffff0000u);
+    x[4] = __uint_as_float(q.z << 16);
+    x[5] = __uint_as_float(q.z & 0xffff0000u);
+    x[6] = __uint_as_float(q.w << 16);
+    x[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+}
+
+__device__ __forceinline__ uint4 ld16(const char* p) {
+  return *reinterpret_cast<const uint4*>(p);
+}
+__device__ __forceinline__ void st16(char* p, const uint4& v) {
+  *reinterpret_cast<uint4*>(p) = v;
+}
+
+// Variance over the D channels of one normalised token (Eq. 9-10; the square root is
+// taken later, once per token).  zbar = (x - mn) * iv.  Two passes: the mean first
+// (any error in it only enters the variance to second order, so the cheap fma form
+// seeded with bias = sum_j -(mn_j*iv_j) is used), then the centred sum of squares
+// from the exactly subtracted (x - mn).  The row is spread over LPR lanes.
+template <int LPR, int VEC>
+__device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&mn)[VEC],
+                                           const float (&iv)[VEC], float bias, float inv_D,
+                                           float inv_dof) {
+  float s = bias;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
+  s = group_sum<LPR>(s);
+  const float mean = s * inv_D;
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    const float d = fmaf(x[j] - mn[j], iv[j], -mean);
+    ss = fmaf(d, d, ss);
+  }
+  ss = group_sum<LPR>(ss);
+  return ss * inv_dof;
+}
+
+template <int VEC>
+struct TStats {  // running per-channel min/max of the lane's VEC channels (Eq. 7-8)
+  float mn[VEC], mx[VEC];
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      mn[j] = INFINITY;
+      mx[j] = -INFINITY;
+    }
+  }
+};
+
+template <int VEC>
+struct TRef {  // reference statistics as Eq. 9 consumes them: zbar = (x - mn) * iv
+  float mn[VEC], iv[VEC];
+  float bias;
+  __device__ __forceinline__ void from(const TStats<VEC>& s) {
+    bias = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      mn[j] = s.mn[j];
+      iv[j] = (s.mx[j] > s.mn[j]) ? 1.0f / (s.mx[j] - s.mn[j]) : 0.f;  // constant channel -> 0
+      bias -= mn[j] * iv[j];
+    }
+  }
+};
+
+// dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane.
+template <int LPR>
+__device__ __forceinline__ void copy_rows_kv(const char* __restrict__ ks, const char* __restrict__ vs,
+                                             int64_t sst, char* __restrict__ kd,
+                                             char* __restrict__ vd, int64_t dst_st, int64_t nrows,
+                                             int tid, int nthreads) {
+  const int cl = tid % LPR;
+  const int64_t ng = nthreads / LPR;
+  for (int64_t r = tid / LPR; r < nrows; r += ng) {
+    const uint4 a = ld16(ks + r * sst + cl * 16);
+    const uint4 b = ld16(vs + r * sst + cl * 16);
+    st16(kd + r * dst_st + cl * 16, a);
+    st16(vd + r * dst_st + cl * 16, b);
+  }
+}
+
+inline int lanes_per_row(int D, int esize) {
+  switch ((int64_t)D * esize) {
+    case 64: return 4;
+    case 128: return 8;
+    case 256: return 16;
+    case 512: return 32;
+    default: return 0;
+  }
+}
+
+}  // namespace lagkv

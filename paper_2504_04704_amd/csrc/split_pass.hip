@@ -1,0 +1,275 @@
+// Tensor-split streaming LagKV kernel for gfx950 (the default one-shot kernel).
+//
+// Like the streaming kernel in fused_pass.hip a workgroup walks a segment of one
+// stream backwards and scores chunk p with the statistics of chunk p+1 while folding
+// chunk p's own min/max for chunk p-1, so every input byte is streamed once.  Here the
+// first half of the wavefronts handles only K rows and the second half only V rows:
+// a lane carries the statistics of ONE tensor, which halves the register footprint and
+// lets 16 wavefronts share a CU (4 per SIMD) with eight 16-byte loads in flight each.
+// The kept rows are re-read for the compaction right after the selection; the chunks
+// in flight (2 workgroups per CU x 2 x L rows) are sized to stay within the 256 MiB
+// memory-side cache, so that re-read does not go to HBM.
+#include "lagkv_internal.hpp"
+#include "row_ops.hpp"
+#include "wave_ops.hpp"
+
+#ifndef LAGKV_SPLIT_U
+#define LAGKV_SPLIT_U 4      // rows in flight per lane
+#endif
+#ifndef LAGKV_SPLIT_UG
+#define LAGKV_SPLIT_UG 8     // kept rows in flight per lane in the compaction
+#endif
+#ifndef LAGKV_NT_STORE
+#define LAGKV_NT_STORE 1     // 1: non-temporal stores for the output rows (never re-read)
+#endif
+#ifndef LAGKV_SPLIT_WPE
+#define LAGKV_SPLIT_WPE 4    // wavefronts per SIMD the register budget is set for
+#endif
+
+namespace lagkv {
+
+__device__ __forceinline__ void st16_out(char* p, const uint4& v) {
+#if LAGKV_NT_STORE
+  __builtin_nontemporal_store(v.x, reinterpret_cast<uint32_t*>(p));
+  __builtin_nontemporal_store(v.y, reinterpret_cast<uint32_t*>(p) + 1);
+  __builtin_nontemporal_store(v.z, reinterpret_cast<uint32_t*>(p) + 2);
+  __builtin_nontemporal_store(v.w, reinterpret_cast<uint32_t*>(p) + 3);
+#else
+  st16(p, v);
+#endif
+}
+
+struct SplitLds {
+  int off_vK, off_vV, off_list, off_stat, total;  // bytes
+};
+__host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw) {
+  SplitLds l;
+  const int lp = (L + 3) & ~3, kp = (k + 3) & ~3;
+  l.off_vK = 0;
+  l.off_vV = lp * 4;
+  l.off_list = 2 * lp * 4;
+  l.off_stat = l.off_list + kp * 4;
+  l.total = l.off_stat + nw * 2 * D * 4;  // [wave][mn|mx][D]
+  return l;
+}
+
+template <typename ET, int LPR>
+__global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const PassArgs a) {
+  constexpr int VEC = ET::VEC;
+  constexpr int RPW = kWave / LPR;
+  constexpr int U = LAGKV_SPLIT_U;
+  extern __shared__ float4 lds_raw[];
+  char* lds = reinterpret_cast<char*>(lds_raw);
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nw = nthreads >> 6, G = nw >> 1;
+  const SplitLds lay = split_lds(a.D, a.L, a.k, nw);
+  float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
+  float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
+  uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+
+  const int tensor = wave >= G ? 1 : 0;  // 0: this wavefront handles K rows, 1: V rows
+  const int gslot = wave - tensor * G;
+  const int rl = lane / LPR, cl = lane % LPR;
+  const int R = G * RPW;                  // rows of one tensor covered per step
+  const int row0 = gslot * RPW + rl;
+  const int L = a.L, k = a.k, S = a.S;
+  const int n_iter = (L + R - 1) / R;
+  const int64_t rowbytes = (int64_t)LPR * 16;
+  const int64_t coff = (int64_t)cl * 16;
+
+  const int64_t stream = blockIdx.x / a.nseg;
+  const int seg = blockIdx.x % a.nseg;
+  const int64_t b = stream / a.H, h = stream % a.H;
+  const char* kin = a.K + b * a.sb + h * a.sh;
+  const char* vin = a.V + b * a.sb + h * a.sh;
+  const char* tin = tensor ? vin : kin;
+  const bool gather = a.K_out != nullptr;
+  char* kout = gather ? a.K_out + stream * a.T_out * rowbytes : nullptr;
+  char* vout = gather ? a.V_out + stream * a.T_out * rowbytes : nullptr;
+  char* tout = tensor ? vout : kout;
+  int32_t* iout = (gather && a.idx_out) ? a.idx_out + stream * a.T_out : nullptr;
+  float* sout = a.scores ? a.scores + stream * a.n_s * L : nullptr;
+  float* myvar = tensor ? vV : vK;
+  const float inv_D = 1.0f / (float)a.D;
+  const float inv_dof = 1.0f / (float)(a.D - a.ddof);
+  const bool local = a.variant == 1;  // Eq. 14-15: statistics from the chunk itself
+
+  for (int i = tid; i < k; i += nthreads) list[i] = 0;
+
+  // sink rows and the sliding window (last full chunk + remainder) are plain copies
+  if (gather && seg == 0 && S > 0) {
+    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, tid, nthreads);
+    if (iout)
+      for (int i = tid; i < S; i += nthreads) iout[i] = i;
+  }
+  if (gather && seg == a.nseg - 1) {
+    const int64_t w0 = S + a.n_s * L, o0 = S + a.n_s * k, nwin = a.T - w0;
+    copy_rows_kv<LPR>(kin + w0 * a.st, vin + w0 * a.st, a.st, kout + o0 * rowbytes,
+                      vout + o0 * rowbytes, rowbytes, nwin, tid, nthreads);
+    if (iout)
+      for (int64_t i = tid; i < nwin; i += nthreads) iout[o0 + i] = (int32_t)(w0 + i);
+  }
+
+  const int64_t p0 = (int64_t)seg * a.n_s / a.nseg;
+  const int64_t p1 = (int64_t)(seg + 1) * a.n_s / a.nseg;
+
+  TStats<VEC> acc;
+  TRef<VEC> ref;
+
+  // one pass over the L rows of this wavefront's tensor; rows past L repeat the last
+  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+    constexpr bool STATS = decltype(stats_tag)::value, SCORE = decltype(score_tag)::value;
+    const char* base = tin + row * a.st + coff;
+    for (int it = 0; it < n_iter; it += U) {
+      uint4 q[U];
+      int r[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        r[u] = row0 + (it + u) * R;
+        q[u] = ld16(base + (int64_t)(r[u] < L ? r[u] : L - 1) * a.st);
+      }
+#pragma unroll
+      for (int u = 0; u < U; u += 2) {
+        float x0[VEC], x1[VEC];
+        unpack<ET>(q[u], x0);
+        unpack<ET>(q[u + 1], x1);
+        if constexpr (STATS) {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) {
+            acc.mn[j] = fminf(fminf(acc.mn[j], x0[j]), x1[j]);
+            acc.mx[j] = fmaxf(fmaxf(acc.mx[j], x0[j]), x1[j]);
+          }
+        }
+        if constexpr (SCORE) {
+          const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          if (cl == 0) {
+            if (r[u] < L) myvar[r[u]] = v0;
+            if (r[u + 1] < L) myvar[r[u + 1]] = v1;
+          }
+        }
+      }
+    }
+  };
+  // combine acc over the row groups of a wavefront and the wavefronts of the tensor
+  // group; one __syncthreads inside (it also publishes the variances)
+  auto fold = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int m = LPR; m < kWave; m <<= 1) {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        acc.mn[j] = fminf(acc.mn[j], __shfl_xor(acc.mn[j], m));
+        acc.mx[j] = fmaxf(acc.mx[j], __shfl_xor(acc.mx[j], m));
+      }
+    }
+    if (G > 1) {
+      if (rl == 0) {
+        float* w = statbuf + (size_t)wave * 2 * a.D + cl * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          w[j] = acc.mn[j];
+          w[a.D + j] = acc.mx[j];
+        }
+      }
+      __syncthreads();
+      for (int g = 0; g < G; ++g) {
+        const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          acc.mn[j] = fminf(acc.mn[j], rd[j]);
+          acc.mx[j] = fmaxf(acc.mx[j], rd[j + a.D]);
+        }
+      }
+    } else {
+      __syncthreads();
+    }
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+
+  if (!local) {  // statistics of the chunk after the segment: the first reference
+    acc.reset();
+    scan(S + p1 * L, T_{}, F_{});
+    fold();
+    ref.from(acc);
+    __syncthreads();  // statbuf is rewritten by the next fold
+  }
+
+  for (int64_t p = p1 - 1; p >= p0; --p) {
+    const int64_t crow = S + p * L;
+    acc.reset();
+    if (local) {
+      scan(crow, T_{}, F_{});
+      fold();
+      ref.from(acc);
+      scan(crow, F_{}, T_{});
+      __syncthreads();
+    } else {
+      scan(crow, T_{}, T_{});
+      fold();
+    }
+    if (wave == 0) {
+      wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
+    } else if (!local) {
+      ref.from(acc);  // chunk p is the reference of chunk p-1
+    }
+    __syncthreads();
+    if (gather) {
+      const char* src = tin + crow * a.st + coff;
+      char* dst = tout + (S + p * k) * rowbytes + coff;
+      constexpr int UG = LAGKV_SPLIT_UG;
+      for (int s0 = row0; s0 < k; s0 += UG * R) {
+        uint4 g[UG];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+          const int s = s0 + u * R;
+          g[u] = ld16(src + (int64_t)list[s < k ? s : s0] * a.st);
+        }
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+          const int s = s0 + u * R;
+          if (s < k) st16_out(dst + (int64_t)s * rowbytes, g[u]);
+        }
+      }
+      if (iout)
+        for (int i = tid; i < k; i += nthreads)
+          iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
+    }
+    if (wave == 0 && !local) ref.from(acc);
+  }
+}
+
+// ------------------------------------------------------------------------ host side
+size_t split_lds_bytes(int D, int L, int k, int nwaves) {
+  return (size_t)split_lds(D, L, k, nwaves).total;
+}
+
+template <typename ET>
+static hipError_t launch_split_t(const PassArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
+                                 hipStream_t s) {
+  switch (lpr) {
+    case 4: split_pass_kernel<ET, 4><<<grid, block, lds, s>>>(a); break;
+    case 8: split_pass_kernel<ET, 8><<<grid, block, lds, s>>>(a); break;
+    case 16: split_pass_kernel<ET, 16><<<grid, block, lds, s>>>(a); break;
+    case 32: split_pass_kernel<ET, 32><<<grid, block, lds, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_split_pass(const PassArgs& a, hipStream_t s) {
+  const int lpr = lanes_per_row(a.D, a.esize);
+  const int64_t nblocks = (int64_t)a.B * a.H * a.nseg;
+  if (lpr == 0 || nblocks <= 0 || nblocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (a.nwaves != 2 && a.nwaves != 4 && a.nwaves != 8) return hipErrorInvalidValue;
+  const size_t lds = split_lds_bytes(a.D, a.L, a.k, a.nwaves);
+  if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);
+  return a.esize == 4 ? launch_split_t<F32>(a, lpr, grid, block, lds, s)
+                      : launch_split_t<BF16>(a, lpr, grid, block, lds, s);
+}
+
+}  // namespace lagkv

@@ -91,12 +91,13 @@ __global__ void __launch_bounds__(256) staged_score_kernel(const PassArgs a, int
     s = wave_sum(s);
     t = wave_sum(t);
     if (lane == 0) {
-      sK[r] = sqrtf(s * inv_dof);
-      sV[r] = sqrtf(t * inv_dof);
+      sK[r] = s * inv_dof;  // variance; the square root is taken with the softmax
+      sV[r] = t * inv_dof;
     }
   }
   __syncthreads();
-  if (wave == 0) wave_chunk_softmax(sK, sV, L, scores + (stream * a.n_s + p) * L, lane);
+  if (wave == 0)
+    wave_score_select_any(sK, sV, L, 0, false, scores + (stream * a.n_s + p) * L, nullptr, nullptr, lane);
 }
 
 // One wavefront per (stream, chunk): top-k of L scores, ascending absolute positions.
@@ -112,7 +113,7 @@ __global__ void __launch_bounds__(64) select_kernel(const float* __restrict__ sc
   for (int t = lane; t < L; t += kWave) sc[t] = src[t];
   for (int i = lane; i < k; i += kWave) list[i] = 0;
   __syncthreads();
-  wave_select_any(sc, L, k, list, lane);
+  wave_topk_scores(sc, L, k, list, lane);
   __syncthreads();
   for (int i = lane; i < k; i += kWave)
     kept[chunk * k + i] = (int32_t)(row0 + p * L + list[i]);
