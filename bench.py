@@ -96,6 +96,17 @@ def bench_compress(args):
         lagkv.tune(lagkv.TUNE_WAVES, args.waves)
     if args.segments:
         lagkv.tune(lagkv.TUNE_SEGMENTS, args.segments)
+    if not args.no_page_warmup:
+        # The first allocation a process makes on a freshly started GPU is backed by a worse
+        # physical page layout than memory that has been allocated and released once (the same
+        # kernel on the same bytes is ~8 % slower on it).  Cycle the working set through the
+        # allocator once before the buffers that are timed are created.
+        for _ in range(3):
+            scratch = torch.empty(int(1.3 * cfg.streams * cfg.T * cfg.D * 2 * 2), dtype=torch.uint8, device=dev)
+            scratch.fill_(1)
+            torch.cuda.synchronize()
+            del scratch
+            torch.cuda.empty_cache()
     t0 = time.perf_counter()
     K, V = synth.make_kv(cfg, device=dev)
     torch.cuda.synchronize()
@@ -260,6 +271,8 @@ def main():
     ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--cpu-streams", type=int, default=32)
+    ap.add_argument("--no-page-warmup", action="store_true",
+                    help="skip the allocate/release cycle done before the timed buffers are created")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--decode-batch", type=int, default=0)

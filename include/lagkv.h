@@ -167,11 +167,8 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const v
  * kernels do not support.
  */
 enum {
-  LAGKV_TUNE_PATH = 0,       /* 0 auto; 1 a fused kernel (error if the shape is unsupported); 2 the
-                                three-kernel path; one-shot pass only: 3 the streaming fused kernel,
-                                4 the chunk-resident fused kernel (error if unsupported), 5 the
-                                tensor-split streaming kernel (the automatic choice)               */
-  LAGKV_TUNE_WAVES = 1,      /* wavefronts cooperating on one chunk in the fused kernel: 1,2,4,8 */
+  LAGKV_TUNE_PATH = 0,       /* 0 auto, 1 force the fused kernels (error if unsupported), 2 force the three-kernel path */
+  LAGKV_TUNE_WAVES = 1,      /* wavefronts per workgroup of the fused kernels: 1 (append only), 2, 4, 8 */
   LAGKV_TUNE_SEGMENTS = 2,   /* segments each stream is cut into by the fused kernel (>= 1)         */
   LAGKV_TUNE_COUNT = 3
 };

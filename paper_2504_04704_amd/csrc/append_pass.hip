@@ -1,17 +1,12 @@
-// Fused LagKV kernels for gfx950: one streaming read of K and V per pass.
+// Decode-time LagKV kernel for gfx950: append rows to a dense cache and compress, in
+// place, every chunk of the tail that has a reference chunk.
 //
-// Row layout: a token row (D channels) is 16*LPR bytes and is held by LPR
-// consecutive lanes, 16 bytes each, so one wave64 load instruction fetches 64/LPR
-// whole rows and the per-token channel reductions of Eq. 10 are DPP reductions over
-// LPR lanes.  The per-channel min/max of Eq. 7-8 accumulate in registers down the
-// rows a lane visits and are folded across row groups and wavefronts once per chunk.
-//
-// fused_pass_kernel walks a segment of one stream BACKWARDS: while chunk p is
-// scored with the statistics of chunk p+1 (already in registers) its own min/max are
-// collected for chunk p-1, so every input byte is fetched from HBM once.  The only
-// extra read is one statistics-only chunk per segment.  After a chunk is scored one
-// wavefront runs the chunk softmax (Eq. 10-11) and the top-k; then all wavefronts
-// copy the kept rows (a re-read that is served by the caches) to the dense output.
+// Row layout (shared with the one-shot kernel): a token row (D channels) is 16*LPR bytes
+// and is held by LPR consecutive lanes, 16 bytes each, so one wave64 load instruction
+// fetches 64/LPR whole rows and the per-token channel reductions of Eq. 10 are DPP
+// reductions over LPR lanes.  The per-channel min/max of Eq. 7-8 accumulate in
+// registers down the rows a lane visits and are folded across row groups and
+// wavefronts once per chunk.
 #include "lagkv_internal.hpp"
 #include "row_ops.hpp"
 #include "wave_ops.hpp"
@@ -46,9 +41,9 @@ struct RefStats {
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
       mnK[j] = s.mnK[j];
-      ivK[j] = (s.mxK[j] > s.mnK[j]) ? 1.0f / (s.mxK[j] - s.mnK[j]) : 0.f;
+      ivK[j] = inv_range(s.mnK[j], s.mxK[j]);
       mnV[j] = s.mnV[j];
-      ivV[j] = (s.mxV[j] > s.mnV[j]) ? 1.0f / (s.mxV[j] - s.mnV[j]) : 0.f;
+      ivV[j] = inv_range(s.mnV[j], s.mxV[j]);
       biasK -= mnK[j] * ivK[j];
       biasV -= mnV[j] * ivV[j];
     }
@@ -198,111 +193,6 @@ __host__ __device__ inline LdsLayout lds_layout(int D, int L, int k, int nw) {
   l.off_stat = l.off_list + kp * 4;
   l.total = l.off_stat + (nw > 1 ? nw * 4 * D * 4 : 0);
   return l;
-}
-
-template <typename ET, int LPR>
-__global__ void __launch_bounds__(512) fused_pass_kernel(const PassArgs a) {
-  constexpr int VEC = ET::VEC;
-  extern __shared__ float4 lds_raw[];
-  char* lds = reinterpret_cast<char*>(lds_raw);
-  const Geometry g = make_geometry<LPR>();
-  const LdsLayout lay = lds_layout(a.D, a.L, a.k, g.nw);
-  float* sK = reinterpret_cast<float*>(lds + lay.off_sK);
-  float* sV = reinterpret_cast<float*>(lds + lay.off_sV);
-  uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
-  float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
-
-  const int tid = threadIdx.x, nthreads = blockDim.x;
-  const int64_t stream = blockIdx.x / a.nseg;
-  const int seg = blockIdx.x % a.nseg;
-  const int64_t b = stream / a.H, h = stream % a.H;
-  const char* kin = a.K + b * a.sb + h * a.sh;
-  const char* vin = a.V + b * a.sb + h * a.sh;
-  const int64_t rowbytes = (int64_t)LPR * 16;
-  const bool gather = a.K_out != nullptr;
-  char* kout = gather ? a.K_out + stream * a.T_out * rowbytes : nullptr;
-  char* vout = gather ? a.V_out + stream * a.T_out * rowbytes : nullptr;
-  int32_t* iout = (gather && a.idx_out) ? a.idx_out + stream * a.T_out : nullptr;
-  float* sout = a.scores ? a.scores + stream * a.n_s * a.L : nullptr;
-  const int L = a.L, k = a.k, S = a.S;
-  const float inv_D = 1.0f / (float)a.D;
-  const float inv_dof = 1.0f / (float)(a.D - a.ddof);
-
-  for (int i = tid; i < k; i += nthreads) list[i] = 0;
-
-  // sink rows and the sliding window (last full chunk + remainder) are plain copies
-  if (gather && seg == 0 && S > 0) {
-    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, tid, nthreads);
-    if (iout)
-      for (int i = tid; i < S; i += nthreads) iout[i] = i;
-  }
-  if (gather && seg == a.nseg - 1) {
-    const int64_t w0 = S + a.n_s * L, o0 = S + a.n_s * k, nwin = a.T - w0;
-    copy_rows_kv<LPR>(kin + w0 * a.st, vin + w0 * a.st, a.st, kout + o0 * rowbytes,
-                      vout + o0 * rowbytes, rowbytes, nwin, tid, nthreads);
-    if (iout)
-      for (int64_t i = tid; i < nwin; i += nthreads) iout[o0 + i] = (int32_t)(w0 + i);
-  }
-
-  const int64_t p0 = (int64_t)seg * a.n_s / a.nseg;
-  const int64_t p1 = (int64_t)(seg + 1) * a.n_s / a.nseg;
-
-  ChanStats<VEC> acc;
-  RefStats<VEC> ref;
-  const bool local = a.variant == 1;  // Eq. 14-15: statistics from the chunk itself
-  if (!local) {
-    // statistics of the chunk after the segment: the first reference
-    acc.reset();
-    const int64_t c = (S + p1 * L) * a.st;
-    scan_chunk<ET, LPR, true, false>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
-    fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
-    ref.from(acc);
-    __syncthreads();  // statbuf is rewritten by the next fold
-  }
-
-  for (int64_t p = p1 - 1; p >= p0; --p) {
-    const int64_t c = (S + p * L) * a.st;
-    acc.reset();
-    if (local) {
-      scan_chunk<ET, LPR, true, false>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
-      fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
-      ref.from(acc);
-      scan_chunk<ET, LPR, false, true>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
-      __syncthreads();
-    } else {
-      scan_chunk<ET, LPR, true, true>(kin + c, vin + c, a.st, L, g, acc, ref, inv_D, inv_dof, sK, sV);
-      fold_stats<LPR, VEC>(acc, g, statbuf, a.D);  // barrier inside: spreads are visible
-      ref.from(acc);                               // chunk p is the reference of chunk p-1
-    }
-    if (g.wave == 0)
-      wave_score_select_any(sK, sV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, g.lane);
-    __syncthreads();
-    if (gather) {
-      const char* ksrc = kin + c;
-      const char* vsrc = vin + c;
-      char* kd = kout + (S + p * k) * rowbytes;
-      char* vd = vout + (S + p * k) * rowbytes;
-      const int64_t coff = (int64_t)g.cl * 16;
-      for (int s0 = g.row0; s0 < k; s0 += 2 * g.rps) {
-        const int s1 = s0 + g.rps;
-        const int64_t t0 = list[s0];
-        const int64_t t1 = list[s1 < k ? s1 : s0];
-        const uint4 ka = ld16(ksrc + t0 * a.st + coff);
-        const uint4 va = ld16(vsrc + t0 * a.st + coff);
-        const uint4 kb = ld16(ksrc + t1 * a.st + coff);
-        const uint4 vb = ld16(vsrc + t1 * a.st + coff);
-        st16(kd + s0 * rowbytes + coff, ka);
-        st16(vd + s0 * rowbytes + coff, va);
-        if (s1 < k) {
-          st16(kd + s1 * rowbytes + coff, kb);
-          st16(vd + s1 * rowbytes + coff, vb);
-        }
-      }
-      if (iout)
-        for (int i = tid; i < k; i += nthreads)
-          iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
-    }
-  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -460,31 +350,6 @@ bool fused_supported(int D, int esize, int64_t sb, int64_t sh, int64_t st, const
 
 size_t fused_lds_bytes(int D, int L, int k, int nwaves) {
   return (size_t)lds_layout(D, L, k, nwaves).total;
-}
-
-template <typename ET>
-static hipError_t launch_pass_t(const PassArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
-                                hipStream_t s) {
-  switch (lpr) {
-    case 4: fused_pass_kernel<ET, 4><<<grid, block, lds, s>>>(a); break;
-    case 8: fused_pass_kernel<ET, 8><<<grid, block, lds, s>>>(a); break;
-    case 16: fused_pass_kernel<ET, 16><<<grid, block, lds, s>>>(a); break;
-    case 32: fused_pass_kernel<ET, 32><<<grid, block, lds, s>>>(a); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
-}
-
-hipError_t launch_fused_pass(const PassArgs& a, hipStream_t s) {
-  const int lpr = lanes_per_row(a.D, a.esize);
-  const int64_t streams = (int64_t)a.B * a.H;
-  const int64_t nblocks = streams * a.nseg;
-  if (lpr == 0 || nblocks <= 0 || nblocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  const size_t lds = fused_lds_bytes(a.D, a.L, a.k, a.nwaves);
-  if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);
-  return a.esize == 4 ? launch_pass_t<F32>(a, lpr, grid, block, lds, s)
-                      : launch_pass_t<BF16>(a, lpr, grid, block, lds, s);
 }
 
 template <typename ET>

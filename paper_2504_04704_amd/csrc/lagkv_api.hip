@@ -94,37 +94,14 @@ int pick_waves(const Norm& n) {
   return nw;
 }
 
-bool fused_fits(const Norm& n) { return fused_lds_bytes(n.D, n.L, n.k, 1) <= (size_t)kMaxLdsBytes; }
+bool fused_fits(const Norm& n) {
+  return split_lds_bytes(n.D, n.L, n.k, 2) <= (size_t)kMaxLdsBytes &&
+         fused_lds_bytes(n.D, n.L, n.k, 1) <= (size_t)kMaxLdsBytes;
+}
 
 bool staged_fits(const Norm& n) {
   return staged_score_lds_bytes(n.D, n.L) <= (size_t)kMaxLdsBytes &&
          ((size_t)n.L + n.k) * 4 <= (size_t)kMaxLdsBytes;
-}
-
-int pick_segments(const Norm& n, int64_t n_s);
-
-// 0 = the chunk-resident kernel does not serve this shape
-int resident_nw(const Norm& n) {
-  const int nw = resident_waves(n.D, n.esize, n.L);
-  if (nw == 0 || resident_lds_bytes(n.D, n.L, n.k, nw) > (size_t)kMaxLdsBytes) return 0;
-  return nw;
-}
-
-// The resident kernel runs 8 wavefronts per CU: cut streams into segments only until
-// every CU of the chip (256) has its workgroups, and keep segments >= 4 chunks.
-int pick_segments_resident(const Norm& n, int64_t n_s, int nw) {
-  int64_t nseg;
-  if (g_tune[LAGKV_TUNE_SEGMENTS]) {
-    nseg = g_tune[LAGKV_TUNE_SEGMENTS];
-  } else {
-    const int64_t capacity = 256 * (8 / nw > 1 ? 8 / nw : 1);
-    nseg = n.streams >= capacity ? 1 : (capacity + n.streams - 1) / n.streams;
-    const int64_t cap = n_s / 4 > 1 ? n_s / 4 : 1;
-    if (nseg > cap) nseg = cap;
-  }
-  if (nseg > n_s) nseg = n_s;
-  if (nseg < 1) nseg = 1;
-  return (int)nseg;
 }
 
 // Wavefronts per workgroup of the tensor-split kernel (0 = its LDS need does not fit).
@@ -153,42 +130,11 @@ int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   return (int)nseg;
 }
 
-// Launch one fused pass with the kernel the tuning and the shape select.
-// force: 0/1 automatic (tensor-split kernel), 3 streaming, 4 chunk-resident (error if
-// unsupported), 5 tensor-split.
-int launch_fused_any(PassArgs& a, const Norm& n, int64_t force, hipStream_t s) {
-  if (force == 4) {
-    const int rnw = resident_nw(n);
-    if (rnw == 0) return LAGKV_ESHAPE;
-    a.nwaves = rnw;
-    a.nseg = pick_segments_resident(n, a.n_s, rnw);
-    return launch_resident_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
-  }
-  const int snw = split_nw(n);
-  if (force == 5 && snw == 0) return LAGKV_ESHAPE;
-  if (snw > 0 && force != 3) {
-    a.nwaves = snw;
-    a.nseg = pick_segments_split(n, a.n_s, snw);
-    return launch_split_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
-  }
-  a.nwaves = pick_waves(n);
-  a.nseg = pick_segments(n, a.n_s);
-  return launch_fused_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
-}
-
-int pick_segments(const Norm& n, int64_t n_s) {
-  int64_t nseg;
-  if (g_tune[LAGKV_TUNE_SEGMENTS]) {
-    nseg = g_tune[LAGKV_TUNE_SEGMENTS];
-  } else {
-    // enough workgroups to fill 256 CUs several times over, segments of >= 8 chunks
-    nseg = (2048 + n.streams - 1) / n.streams;
-    const int64_t cap = n_s / 8 > 1 ? n_s / 8 : 1;
-    if (nseg > cap) nseg = cap;
-  }
-  if (nseg > n_s) nseg = n_s;
-  if (nseg < 1) nseg = 1;
-  return (int)nseg;
+// Launch the one-shot fused kernel.
+int launch_fused_any(PassArgs& a, const Norm& n, hipStream_t s) {
+  a.nwaves = split_nw(n);
+  a.nseg = pick_segments_split(n, a.n_s, a.nwaves);
+  return launch_split_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
 }
 
 // Workspace of the three-kernel path for one pass: [scores][kept]
@@ -308,8 +254,8 @@ int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T, 
   const int64_t force = g_tune[LAGKV_TUNE_PATH];
   const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, K, V, nullptr, nullptr);
-  if (force != 0 && force != 2 && !fused_ok) return LAGKV_ESHAPE;
-  if (fused_ok && force != 2) return launch_fused_any(a, n, force, s);
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != 2) return launch_fused_any(a, n, s);
   if (!staged_fits(n)) return LAGKV_ESHAPE;
   return hip_status(launch_staged_score(a, n.S, scores, s));
 }
@@ -365,8 +311,8 @@ int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t 
   const int64_t force = g_tune[LAGKV_TUNE_PATH];
   const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, K, V, K_out, V_out);
-  if (force != 0 && force != 2 && !fused_ok) return LAGKV_ESHAPE;
-  if (fused_ok && force != 2) return launch_fused_any(a, n, force, s);
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != 2) return launch_fused_any(a, n, s);
   if (!staged_fits(n)) return LAGKV_ESHAPE;
   const StagedWs w = staged_ws(n, pl.n_scored, scores_out == nullptr);
   if (!ws || ws_bytes < w.total || !aligned_to(ws, 16)) return LAGKV_EWORKSPACE;
@@ -413,7 +359,7 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
   const int64_t force = g_tune[LAGKV_TUNE_PATH];
   const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, c->K, c->V, K_new, V_new);
-  if (force != 0 && force != 2 && !fused_ok) return LAGKV_ESHAPE;
+  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
   hipError_t e = hipSuccess;
   if (fused_ok && force != 2) {
     if (n_new > 0 || q > 0) {
@@ -513,7 +459,7 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
 
 int lagkv_tune(int key, int64_t value) {
   if (key < 0 || key >= LAGKV_TUNE_COUNT || value < 0) return LAGKV_EINVAL;
-  if (key == LAGKV_TUNE_PATH && value > 5) return LAGKV_EINVAL;
+  if (key == LAGKV_TUNE_PATH && value > 2) return LAGKV_EINVAL;
   if (key == LAGKV_TUNE_WAVES && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
     return LAGKV_EINVAL;
   if (key == LAGKV_TUNE_SEGMENTS && value > (1 << 20)) return LAGKV_EINVAL;

@@ -1,5 +1,5 @@
 // Internal interface between the C-ABI host layer (lagkv_api.hip) and the kernel
-// launchers (fused_pass.hip, staged_pass.hip).  Not part of the public ABI.
+// launchers (split_pass.hip, append_pass.hip, staged_pass.hip).  Not part of the public ABI.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -53,18 +53,11 @@ bool fused_supported(int D, int esize, int64_t sb, int64_t sh, int64_t st, const
                      const void* V, const void* Ko, const void* Vo);
 size_t fused_lds_bytes(int D, int L, int k, int nwaves);
 
-hipError_t launch_fused_pass(const PassArgs& a, hipStream_t s);
 
-// Tensor-split streaming kernel (default): nwaves in {2,4,8}.
+// One-shot fused kernel (tensor-split streaming): nwaves in {2,4,8}.
 size_t split_lds_bytes(int D, int L, int k, int nwaves);
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s);
 
-// Chunk-resident kernel: wavefronts per workgroup it needs for this row size and lag
-// (0 = shape not served), its LDS need, and its launcher (a.nwaves must equal
-// resident_waves()).
-int resident_waves(int D, int esize, int L);
-size_t resident_lds_bytes(int D, int L, int k, int nwaves);
-hipError_t launch_resident_pass(const PassArgs& a, hipStream_t s);
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s);
 
 // Three-kernel path (any D, any alignment).

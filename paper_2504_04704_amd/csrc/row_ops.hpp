@@ -41,6 +41,19 @@ __device__ __forceinline__ void st16(char* p, const uint4& v) {
   *reinterpret_cast<uint4*>(p) = v;
 }
 
+#ifndef LAGKV_FAST_RCP
+#define LAGKV_FAST_RCP 1
+#endif
+// 1 / (max - min) of a reference channel (Eq. 9), or 0 for a constant channel so that
+// it contributes nothing.  The hardware reciprocal (1 ulp) is used by every kernel.
+__device__ __forceinline__ float inv_range(float mn, float mx) {
+#if LAGKV_FAST_RCP
+  return mx > mn ? __builtin_amdgcn_rcpf(mx - mn) : 0.f;
+#else
+  return mx > mn ? 1.0f / (mx - mn) : 0.f;
+#endif
+}
+
 // Variance over the D channels of one normalised token (Eq. 9-10; the square root is
 // taken later, once per token).  zbar = (x - mn) * iv.  Two passes: the mean first
 // (any error in it only enters the variance to second order, so the cheap fma form
@@ -86,7 +99,7 @@ struct TRef {  // reference statistics as Eq. 9 consumes them: zbar = (x - mn) *
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
       mn[j] = s.mn[j];
-      iv[j] = (s.mx[j] > s.mn[j]) ? 1.0f / (s.mx[j] - s.mn[j]) : 0.f;  // constant channel -> 0
+      iv[j] = inv_range(s.mn[j], s.mx[j]);
       bias -= mn[j] * iv[j];
     }
   }

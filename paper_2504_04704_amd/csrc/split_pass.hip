@@ -53,7 +53,8 @@ __host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw) {
   return l;
 }
 
-template <typename ET, int LPR>
+// EXACT: L is a multiple of the rows one step covers (uniform row addressing).
+template <typename ET, int LPR, bool EXACT>
 __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const PassArgs a) {
   constexpr int VEC = ET::VEC;
   constexpr int RPW = kWave / LPR;
@@ -119,39 +120,61 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   TStats<VEC> acc;
   TRef<VEC> ref;
 
-  // one pass over the L rows of this wavefront's tensor; rows past L repeat the last
-  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+  // One pass over the L rows of this wavefront's tensor.  When L is a multiple of the
+  // rows one step covers (the usual case) a row address is a wave-uniform base plus one
+  // 32-bit lane offset, so no per-lane address arithmetic is needed; steps past the end
+  // repeat the last step.  Otherwise rows past L repeat the last row, lane by lane.
+  constexpr bool exact = EXACT;
+  const uint32_t lane_off = (uint32_t)(row0 * a.st) + (uint32_t)cl * 16u;
+  // consume U loaded rows whose first step is `it` (rows of steps past the end are skipped)
+  auto consume = [&](const uint4 (&q)[U], const int (&r)[U], auto stats_tag, auto score_tag)
+                     __attribute__((always_inline)) {
     constexpr bool STATS = decltype(stats_tag)::value, SCORE = decltype(score_tag)::value;
-    const char* base = tin + row * a.st + coff;
+#pragma unroll
+    for (int u = 0; u < U; u += 2) {
+      float x0[VEC], x1[VEC];
+      unpack<ET>(q[u], x0);
+      unpack<ET>(q[u + 1], x1);
+      if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          acc.mn[j] = fminf(fminf(acc.mn[j], x0[j]), x1[j]);
+          acc.mx[j] = fmaxf(fmaxf(acc.mx[j], x0[j]), x1[j]);
+        }
+      }
+      if constexpr (SCORE) {
+        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        if (cl == 0) {
+          if (r[u] < L) myvar[r[u]] = v0;
+          if (r[u + 1] < L) myvar[r[u + 1]] = v1;
+        }
+      }
+    }
+  };
+  // issue the loads of the U steps that start at step `it` of the chunk whose first row
+  // is `row`
+  auto issue = [&](uint4 (&q)[U], int (&r)[U], int64_t row, int it) __attribute__((always_inline)) {
+    const char* ubase = tin + row * a.st;  // wave-uniform
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if constexpr (exact) {
+        const int step = it + u < n_iter ? it + u : n_iter - 1;
+        r[u] = it + u < n_iter ? row0 + step * R : L;  // L: nothing to store
+        q[u] = ld16(ubase + (int64_t)step * R * a.st + lane_off);
+      } else {
+        r[u] = row0 + (it + u) * R;
+        q[u] = ld16(ubase + coff + (int64_t)(r[u] < L ? r[u] : L - 1) * a.st);
+      }
+    }
+  };
+  // one pass over the L rows of this wavefront's tensor in the chunk whose first row is `row`
+  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
     for (int it = 0; it < n_iter; it += U) {
       uint4 q[U];
       int r[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        r[u] = row0 + (it + u) * R;
-        q[u] = ld16(base + (int64_t)(r[u] < L ? r[u] : L - 1) * a.st);
-      }
-#pragma unroll
-      for (int u = 0; u < U; u += 2) {
-        float x0[VEC], x1[VEC];
-        unpack<ET>(q[u], x0);
-        unpack<ET>(q[u + 1], x1);
-        if constexpr (STATS) {
-#pragma unroll
-          for (int j = 0; j < VEC; ++j) {
-            acc.mn[j] = fminf(fminf(acc.mn[j], x0[j]), x1[j]);
-            acc.mx[j] = fmaxf(fmaxf(acc.mx[j], x0[j]), x1[j]);
-          }
-        }
-        if constexpr (SCORE) {
-          const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-          const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-          if (cl == 0) {
-            if (r[u] < L) myvar[r[u]] = v0;
-            if (r[u + 1] < L) myvar[r[u + 1]] = v1;
-          }
-        }
-      }
+      issue(q, r, row, it);
+      consume(q, r, stats_tag, score_tag);
     }
   };
   // combine acc over the row groups of a wavefront and the wavefronts of the tensor
@@ -190,55 +213,63 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   using T_ = std::true_type;
   using F_ = std::false_type;
 
-  if (!local) {  // statistics of the chunk after the segment: the first reference
-    acc.reset();
-    scan(S + p1 * L, T_{}, F_{});
-    fold();
-    ref.from(acc);
-    __syncthreads();  // statbuf is rewritten by the next fold
-  }
+  auto compact = [&](int64_t p) __attribute__((always_inline)) {
+    const char* src = tin + (S + p * L) * a.st + coff;
+    char* dst = tout + (S + p * k) * rowbytes + coff;
+    constexpr int UG = LAGKV_SPLIT_UG;
+    for (int s0 = row0; s0 < k; s0 += UG * R) {
+      uint4 g[UG];
+#pragma unroll
+      for (int u = 0; u < UG; ++u) {
+        const int s = s0 + u * R;
+        g[u] = ld16(src + (int64_t)list[s < k ? s : s0] * a.st);
+      }
+#pragma unroll
+      for (int u = 0; u < UG; ++u) {
+        const int s = s0 + u * R;
+        if (s < k) st16_out(dst + (int64_t)s * rowbytes, g[u]);
+      }
+    }
+    if (iout)
+      for (int i = tid; i < k; i += nthreads)
+        iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
+  };
 
-  for (int64_t p = p1 - 1; p >= p0; --p) {
-    const int64_t crow = S + p * L;
-    acc.reset();
-    if (local) {
+  if (local) {
+    for (int64_t p = p1 - 1; p >= p0; --p) {
+      const int64_t crow = S + p * L;
+      acc.reset();
       scan(crow, T_{}, F_{});
       fold();
       ref.from(acc);
       scan(crow, F_{}, T_{});
       __syncthreads();
-    } else {
-      scan(crow, T_{}, T_{});
-      fold();
+      if (wave == 0)
+        wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
+      __syncthreads();
+      if (gather) compact(p);
     }
+    return;
+  }
+
+  // statistics of the chunk after the segment: the first reference
+  acc.reset();
+  scan(S + p1 * L, T_{}, F_{});
+  fold();
+  ref.from(acc);
+  __syncthreads();  // statbuf is rewritten by the next fold
+  for (int64_t p = p1 - 1; p >= p0; --p) {
+    acc.reset();
+    scan(S + p * L, T_{}, T_{});
+    fold();  // barrier inside: the variances are visible
     if (wave == 0) {
       wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
-    } else if (!local) {
+    } else {
       ref.from(acc);  // chunk p is the reference of chunk p-1
     }
     __syncthreads();
-    if (gather) {
-      const char* src = tin + crow * a.st + coff;
-      char* dst = tout + (S + p * k) * rowbytes + coff;
-      constexpr int UG = LAGKV_SPLIT_UG;
-      for (int s0 = row0; s0 < k; s0 += UG * R) {
-        uint4 g[UG];
-#pragma unroll
-        for (int u = 0; u < UG; ++u) {
-          const int s = s0 + u * R;
-          g[u] = ld16(src + (int64_t)list[s < k ? s : s0] * a.st);
-        }
-#pragma unroll
-        for (int u = 0; u < UG; ++u) {
-          const int s = s0 + u * R;
-          if (s < k) st16_out(dst + (int64_t)s * rowbytes, g[u]);
-        }
-      }
-      if (iout)
-        for (int i = tid; i < k; i += nthreads)
-          iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
-    }
-    if (wave == 0 && !local) ref.from(acc);
+    if (gather) compact(p);
+    if (wave == 0) ref.from(acc);
   }
 }
 
@@ -250,11 +281,16 @@ size_t split_lds_bytes(int D, int L, int k, int nwaves) {
 template <typename ET>
 static hipError_t launch_split_t(const PassArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
                                  hipStream_t s) {
-  switch (lpr) {
-    case 4: split_pass_kernel<ET, 4><<<grid, block, lds, s>>>(a); break;
-    case 8: split_pass_kernel<ET, 8><<<grid, block, lds, s>>>(a); break;
-    case 16: split_pass_kernel<ET, 16><<<grid, block, lds, s>>>(a); break;
-    case 32: split_pass_kernel<ET, 32><<<grid, block, lds, s>>>(a); break;
+  const bool exact = a.L % ((a.nwaves / 2) * (kWave / lpr)) == 0;
+  switch (lpr * 2 + (exact ? 1 : 0)) {
+    case 8: split_pass_kernel<ET, 4, false><<<grid, block, lds, s>>>(a); break;
+    case 9: split_pass_kernel<ET, 4, true><<<grid, block, lds, s>>>(a); break;
+    case 16: split_pass_kernel<ET, 8, false><<<grid, block, lds, s>>>(a); break;
+    case 17: split_pass_kernel<ET, 8, true><<<grid, block, lds, s>>>(a); break;
+    case 32: split_pass_kernel<ET, 16, false><<<grid, block, lds, s>>>(a); break;
+    case 33: split_pass_kernel<ET, 16, true><<<grid, block, lds, s>>>(a); break;
+    case 64: split_pass_kernel<ET, 32, false><<<grid, block, lds, s>>>(a); break;
+    case 65: split_pass_kernel<ET, 32, true><<<grid, block, lds, s>>>(a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -265,6 +301,8 @@ hipError_t launch_split_pass(const PassArgs& a, hipStream_t s) {
   const int64_t nblocks = (int64_t)a.B * a.H * a.nseg;
   if (lpr == 0 || nblocks <= 0 || nblocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.nwaves != 2 && a.nwaves != 4 && a.nwaves != 8) return hipErrorInvalidValue;
+  // per-lane input offsets are 32 bit: the rows of one step must lie within 2 GiB
+  if (a.st * (int64_t)((a.nwaves / 2) * (kWave / lpr)) >= (1LL << 31)) return hipErrorInvalidValue;
   const size_t lds = split_lds_bytes(a.D, a.L, a.k, a.nwaves);
   if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);

@@ -4,6 +4,7 @@
 // memory.  lagkv_select is always served from here; lagkv_score / lagkv_compress /
 // lagkv_append_and_compress use it for shapes the fused kernels do not cover.
 #include "lagkv_internal.hpp"
+#include "row_ops.hpp"
 #include "wave_ops.hpp"
 
 namespace lagkv {
@@ -64,9 +65,9 @@ __global__ void __launch_bounds__(256) staged_score_kernel(const PassArgs a, int
       hiv = fmaxf(hiv, y);
     }
     mnK[c] = lo;
-    ivK[c] = hi > lo ? 1.0f / (hi - lo) : 0.f;
+    ivK[c] = inv_range(lo, hi);
     mnV[c] = lov;
-    ivV[c] = hiv > lov ? 1.0f / (hiv - lov) : 0.f;
+    ivV[c] = inv_range(lov, hiv);
   }
   __syncthreads();
 

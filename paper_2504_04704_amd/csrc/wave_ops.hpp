@@ -239,8 +239,10 @@ __device__ __forceinline__ void wave_score_select_any(float* vK, const float* vV
 }
 
 // Register-lean dispatch for callers that hold other state in registers: chunks of
-// up to 512 tokens in registers, longer ones through LDS.
-__device__ __forceinline__ void wave_score_select_lean(float* vK, const float* vV, int L, int k,
+// up to 512 tokens in registers, longer ones through LDS.  Deliberately NOT inlined:
+// it runs once per chunk on one wavefront, and keeping it out of line keeps its
+// temporaries out of the caller's register allocation.
+__device__ __attribute__((noinline)) void wave_score_select_lean(float* vK, const float* vV, int L, int k,
                                                        bool do_select, float* gout, uint32_t* list,
                                                        int32_t* slotmap, int lane) {
   if (L <= 128) wave_score_select<2>(vK, vV, L, k, do_select, gout, list, slotmap, lane);

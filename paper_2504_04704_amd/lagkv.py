@@ -22,7 +22,7 @@ OK, EINVAL, ESHAPE, EDTYPE, ECAPACITY, EWORKSPACE, EHIP = range(7)
 F32, BF16 = 0, 1
 SCORE_LAG, SCORE_LOCAL, SCORE_L2 = 0, 1, 2
 TUNE_PATH, TUNE_WAVES, TUNE_SEGMENTS = 0, 1, 2
-PATH_AUTO, PATH_FUSED, PATH_STAGED, PATH_STREAMING, PATH_RESIDENT, PATH_SPLIT = 0, 1, 2, 3, 4, 5
+PATH_AUTO, PATH_FUSED, PATH_STAGED = 0, 1, 2
 
 EXPORTS = ("lagkv_plan", "lagkv_workspace_bytes", "lagkv_score", "lagkv_select", "lagkv_compress",
            "lagkv_append_and_compress", "lagkv_tune", "lagkv_strerror", "lagkv_version")

@@ -164,7 +164,7 @@ def test_append_validation(lib):
 def test_tune_and_strerror(lib):
     assert _status(lagkv.tune, 99, 1) == lagkv.EINVAL
     assert _status(lagkv.tune, lagkv.TUNE_WAVES, 3) == lagkv.EINVAL
-    assert _status(lagkv.tune, lagkv.TUNE_PATH, 9) == lagkv.EINVAL
+    assert _status(lagkv.tune, lagkv.TUNE_PATH, 3) == lagkv.EINVAL
     lagkv.tune(lagkv.TUNE_WAVES, 8); lagkv.tune(lagkv.TUNE_WAVES, 0)
     for s in range(7):
         assert len(lagkv.strerror(s)) > 1
