@@ -95,7 +95,7 @@ int pick_waves(const Norm& n) {
 }
 
 bool fused_fits(const Norm& n) {
-  return split_lds_bytes(n.D, n.L, n.k, 2) <= (size_t)kMaxLdsBytes &&
+  return split_lds_bytes(n.D, n.esize, n.L, n.k, 2) <= (size_t)80 * 1024 &&
          fused_lds_bytes(n.D, n.L, n.k, 1) <= (size_t)kMaxLdsBytes;
 }
 
@@ -109,7 +109,7 @@ int split_nw(const Norm& n) {
   int nw = 8;
   const int64_t t = g_tune[LAGKV_TUNE_WAVES];
   if (t == 2 || t == 4 || t == 8) nw = (int)t;
-  while (nw >= 2 && split_lds_bytes(n.D, n.L, n.k, nw) > (size_t)kMaxLdsBytes) nw >>= 1;
+  while (nw >= 2 && split_lds_bytes(n.D, n.esize, n.L, n.k, nw) > (size_t)80 * 1024) nw >>= 1;
   return nw >= 2 ? nw : 0;
 }
 

@@ -55,7 +55,7 @@ size_t fused_lds_bytes(int D, int L, int k, int nwaves);
 
 
 // One-shot fused kernel (tensor-split streaming): nwaves in {2,4,8}.
-size_t split_lds_bytes(int D, int L, int k, int nwaves);
+size_t split_lds_bytes(int D, int esize, int L, int k, int nwaves);
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s);
 
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s);

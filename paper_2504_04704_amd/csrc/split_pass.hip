@@ -22,6 +22,12 @@
 #ifndef LAGKV_NT_STORE
 #define LAGKV_NT_STORE 1     // 1: non-temporal stores for the output rows (never re-read)
 #endif
+#ifndef LAGKV_SPLIT_RING
+#define LAGKV_SPLIT_RING 8   // 1 KiB LDS slots per wavefront for the asynchronous row loads
+#endif
+#ifndef LAGKV_SPLIT_DMA
+#define LAGKV_SPLIT_DMA 1    // 1: asynchronous global->LDS row loads when the rows of a chunk divide evenly
+#endif
 #ifndef LAGKV_SPLIT_WPE
 #define LAGKV_SPLIT_WPE 4    // wavefronts per SIMD the register budget is set for
 #endif
@@ -39,21 +45,56 @@ __device__ __forceinline__ void st16_out(char* p, const uint4& v) {
 #endif
 }
 
+// ---- asynchronous global -> LDS row loads (gfx950 global_load_lds_dwordx4) -----------
+// A wave-wide load writes lane l's 16 bytes to LDS at base + 16*l without passing
+// through VGPRs and is tracked by the vector-memory counter (vmcnt, in order).  Each
+// wavefront owns a ring of kRing slots of 1 KiB; a slot receives one step (64/LPR rows).
+// The loads are issued kRing-2 steps ahead of the arithmetic.  The LDS reads of landed
+// slots and the variance stores are written in assembly with explicit counter waits so
+// that they are not serialised behind the loads still in flight.
+constexpr int kRing = LAGKV_SPLIT_RING;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+// wait until at most PENDING vector-memory operations are outstanding, then read two
+// landed 16-byte entries
+template <int PENDING>
+__device__ __forceinline__ void lds_read_pair_after(u32x4& a, u32x4& b, uint32_t la, uint32_t lb) {
+  asm volatile(
+      "s_waitcnt vmcnt(%4)\n\t"
+      "ds_read_b128 %0, %2\n\t"
+      "ds_read_b128 %1, %3\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(a), "=&v"(b)
+      : "v"(la), "v"(lb), "n"(PENDING)
+      : "memory");
+}
+__device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
+  asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 struct SplitLds {
-  int off_vK, off_vV, off_list, off_stat, total;  // bytes
+  int off_vK, off_vV, off_list, off_stat, off_ring, total;  // bytes
 };
-__host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw) {
+__host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw, bool ring) {
   SplitLds l;
   const int lp = (L + 3) & ~3, kp = (k + 3) & ~3;
   l.off_vK = 0;
   l.off_vV = lp * 4;
   l.off_list = 2 * lp * 4;
   l.off_stat = l.off_list + kp * 4;
-  l.total = l.off_stat + nw * 2 * D * 4;  // [wave][mn|mx][D]
+  l.off_ring = (l.off_stat + nw * 2 * D * 4 + 1023) & ~1023;  // [wave][mn|mx][D], then the rings
+  l.total = ring ? l.off_ring + nw * kRing * 1024 : l.off_stat + nw * 2 * D * 4;
   return l;
 }
 
-// EXACT: L is a multiple of the rows one step covers (uniform row addressing).
+// EXACT: L is a multiple of the rows one step covers and the LDS ring fits: uniform row
+// addressing and asynchronous loads.  EXACT=false serves any L through registers.
 template <typename ET, int LPR, bool EXACT>
 __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const PassArgs a) {
   constexpr int VEC = ET::VEC;
@@ -65,7 +106,8 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nw = nthreads >> 6, G = nw >> 1;
-  const SplitLds lay = split_lds(a.D, a.L, a.k, nw);
+  constexpr bool use_dma = EXACT && LAGKV_SPLIT_DMA;
+  const SplitLds lay = split_lds(a.D, a.L, a.k, nw, use_dma);
   float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
   float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
   uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
@@ -99,6 +141,12 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const bool local = a.variant == 1;  // Eq. 14-15: statistics from the chunk itself
 
   for (int i = tid; i < k; i += nthreads) list[i] = 0;
+#if defined(LAGKV_DIAG_DESYNC)
+  {  // diagnostic build only: start workgroups at different phases
+    const int d = (int)((blockIdx.x * 2654435761u) >> 29) * LAGKV_DIAG_DESYNC;
+    for (int i = 0; i < d; ++i) __builtin_amdgcn_s_sleep(127);
+  }
+#endif
 
   // sink rows and the sliding window (last full chunk + remainder) are plain copies
   if (gather && seg == 0 && S > 0) {
@@ -119,6 +167,14 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
 
   TStats<VEC> acc;
   TRef<VEC> ref;
+#if defined(LAGKV_DIAG_TIMING)
+  long long t_fold_pre = 0, t_fold_bar = 0, t_mark = wall_clock64();
+#define FOLD_TICK { const long long n_ = wall_clock64(); t_fold_pre += n_ - t_mark; t_mark = n_; }
+#define FOLD_TICK2 { const long long n_ = wall_clock64(); t_fold_bar += n_ - t_mark; t_mark = n_; }
+#else
+#define FOLD_TICK
+#define FOLD_TICK2
+#endif
 
   // One pass over the L rows of this wavefront's tensor.  When L is a multiple of the
   // rows one step covers (the usual case) a row address is a wave-uniform base plus one
@@ -169,13 +225,73 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     }
   };
   // one pass over the L rows of this wavefront's tensor in the chunk whose first row is `row`
-  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+  auto scan_regs = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
     for (int it = 0; it < n_iter; it += U) {
       uint4 q[U];
       int r[U];
       issue(q, r, row, it);
       consume(q, r, stats_tag, score_tag);
     }
+  };
+  // The same pass with asynchronous loads: steps land in this wavefront's LDS ring and
+  // are consumed two at a time, kRing-2 steps behind the loads.
+  const uint32_t ring_lds = lds_offset(lds + lay.off_ring) + (uint32_t)wave * (kRing * 1024u);
+  const uint32_t ring_lane = ring_lds + (uint32_t)lane * 16u;
+  const uint32_t var_lds = lds_offset(myvar) + (uint32_t)row0 * 4u;
+  auto scan_dma = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+    constexpr bool STATS = decltype(stats_tag)::value, SCORE = decltype(score_tag)::value;
+    const char* ubase = tin + row * a.st;  // wave-uniform
+    auto dma = [&](int step) __attribute__((always_inline)) {
+      __builtin_amdgcn_global_load_lds((gptr_t)(ubase + (int64_t)step * R * a.st + lane_off),
+                                       (lptr_t)(lds + lay.off_ring + (wave * kRing + step % kRing) * 1024),
+                                       16, 0, 0);
+    };
+    auto pair = [&](int s, const u32x4& qa, const u32x4& qb) __attribute__((always_inline)) {
+      float x0[VEC], x1[VEC];
+      unpack<ET>(make_uint4(qa.x, qa.y, qa.z, qa.w), x0);
+      unpack<ET>(make_uint4(qb.x, qb.y, qb.z, qb.w), x1);
+      if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          acc.mn[j] = fminf(fminf(acc.mn[j], x0[j]), x1[j]);
+          acc.mx[j] = fmaxf(fmaxf(acc.mx[j], x0[j]), x1[j]);
+        }
+      }
+      if constexpr (SCORE) {
+        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        if (cl == 0) {
+          lds_store_f32(var_lds + (uint32_t)(s * R) * 4u, v0);
+          if (s + 1 < n_iter) lds_store_f32(var_lds + (uint32_t)((s + 1) * R) * 4u, v1);
+        }
+      }
+    };
+    const int ahead = n_iter < kRing ? n_iter : kRing;
+    for (int s = 0; s < ahead; ++s) dma(s);
+    int s = 0;
+    // steady state: steps s and s+1 have landed once at most kRing-2 loads are pending
+    for (; s + kRing + 1 < n_iter; s += 2) {
+      u32x4 qa, qb;
+      lds_read_pair_after<kRing - 2>(qa, qb, ring_lane + (uint32_t)(s % kRing) * 1024u,
+                                     ring_lane + (uint32_t)((s + 1) % kRing) * 1024u);
+      dma(s + kRing);      // the two slots just read are free again
+      dma(s + kRing + 1);
+      pair(s, qa, qb);
+    }
+    // tail: everything has been issued; wait for all of it once
+    for (; s < n_iter; s += 2) {
+      u32x4 qa, qb;
+      const int s1 = s + 1 < n_iter ? s + 1 : s;  // odd step count: the last step twice
+      lds_read_pair_after<0>(qa, qb, ring_lane + (uint32_t)(s % kRing) * 1024u,
+                             ring_lane + (uint32_t)(s1 % kRing) * 1024u);
+      if (s + kRing < n_iter) dma(s + kRing);
+      pair(s, qa, qb);
+    }
+    lds_drain();
+  };
+  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+    if constexpr (use_dma) scan_dma(row, stats_tag, score_tag);
+    else scan_regs(row, stats_tag, score_tag);
   };
   // combine acc over the row groups of a wavefront and the wavefronts of the tensor
   // group; one __syncthreads inside (it also publishes the variances)
@@ -197,7 +313,9 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
           w[a.D + j] = acc.mx[j];
         }
       }
+      FOLD_TICK
       __syncthreads();
+      FOLD_TICK2
       for (int g = 0; g < G; ++g) {
         const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
 #pragma unroll
@@ -258,42 +376,91 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   fold();
   ref.from(acc);
   __syncthreads();  // statbuf is rewritten by the next fold
+#if defined(LAGKV_DIAG_TIMING)
+  // diagnostic build only: per-phase cycle counts of wavefronts 0 and 1, written over the
+  // first entries of the workgroup's output index rows
+  long long t_scan = 0, t_fold = 0, t_sel = 0, t_wait = 0, t_comp = 0;
+#define TICK(acc_) { const long long now_ = wall_clock64(); acc_ += now_ - t_last; t_last = now_; }
+  long long t_last = wall_clock64();
+#else
+#define TICK(acc_)
+#endif
   for (int64_t p = p1 - 1; p >= p0; --p) {
     acc.reset();
     scan(S + p * L, T_{}, T_{});
+    TICK(t_scan)
+#if defined(LAGKV_DIAG_TIMING)
+    t_mark = t_last;
+#endif
     fold();  // barrier inside: the variances are visible
+    TICK(t_fold)
     if (wave == 0) {
       wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
     } else {
       ref.from(acc);  // chunk p is the reference of chunk p-1
     }
+    TICK(t_sel)
     __syncthreads();
+    TICK(t_wait)
     if (gather) compact(p);
     if (wave == 0) ref.from(acc);
+    TICK(t_comp)
   }
+#if defined(LAGKV_DIAG_TIMING)
+  if (iout && lane == 0) {
+    long long* d = reinterpret_cast<long long*>(iout + a.T_out - 256 + 16 * wave);  // inside the window part
+    d[0] = t_scan; d[1] = t_fold; d[2] = t_sel; d[3] = t_wait; d[4] = t_comp; d[5] = t_fold_pre; d[6] = t_fold_bar;
+  }
+#endif
+#undef TICK
 }
 
 // ------------------------------------------------------------------------ host side
-size_t split_lds_bytes(int D, int L, int k, int nwaves) {
-  return (size_t)split_lds(D, L, k, nwaves).total;
+// A workgroup may use up to 80 KiB of LDS so that two of them share the 160 KiB of a CU.
+constexpr size_t kSplitMaxLds = 80 * 1024;
+
+static bool split_exact(int lpr, int L, int nwaves) {
+  return L % ((nwaves / 2) * (kWave / lpr)) == 0;
+}
+// The asynchronous-load variant needs the ring as well; if that does not fit, the
+// register variant (which serves any L) is used.
+static bool split_uses_ring(int D, int L, int k, int nwaves, int lpr) {
+  return LAGKV_SPLIT_DMA && split_exact(lpr, L, nwaves) &&
+         (size_t)split_lds(D, L, k, nwaves, true).total <= kSplitMaxLds;
+}
+
+size_t split_lds_bytes(int D, int esize, int L, int k, int nwaves) {
+  const int lpr = lanes_per_row(D, esize);
+  if (lpr == 0) return (size_t)-1;
+  return (size_t)split_lds(D, L, k, nwaves, split_uses_ring(D, L, k, nwaves, lpr)).total;
+}
+
+template <typename K>
+static hipError_t launch_one(K kernel, const PassArgs& a, dim3 grid, dim3 block, size_t lds,
+                             hipStream_t s) {
+  if (lds > 64 * 1024) {  // beyond the default dynamic LDS limit: opt in (idempotent)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  kernel<<<grid, block, lds, s>>>(a);
+  return hipGetLastError();
 }
 
 template <typename ET>
-static hipError_t launch_split_t(const PassArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
-                                 hipStream_t s) {
-  const bool exact = a.L % ((a.nwaves / 2) * (kWave / lpr)) == 0;
-  switch (lpr * 2 + (exact ? 1 : 0)) {
-    case 8: split_pass_kernel<ET, 4, false><<<grid, block, lds, s>>>(a); break;
-    case 9: split_pass_kernel<ET, 4, true><<<grid, block, lds, s>>>(a); break;
-    case 16: split_pass_kernel<ET, 8, false><<<grid, block, lds, s>>>(a); break;
-    case 17: split_pass_kernel<ET, 8, true><<<grid, block, lds, s>>>(a); break;
-    case 32: split_pass_kernel<ET, 16, false><<<grid, block, lds, s>>>(a); break;
-    case 33: split_pass_kernel<ET, 16, true><<<grid, block, lds, s>>>(a); break;
-    case 64: split_pass_kernel<ET, 32, false><<<grid, block, lds, s>>>(a); break;
-    case 65: split_pass_kernel<ET, 32, true><<<grid, block, lds, s>>>(a); break;
+static hipError_t launch_split_t(const PassArgs& a, int lpr, bool ring, dim3 grid, dim3 block,
+                                 size_t lds, hipStream_t s) {
+  switch (lpr * 2 + (ring ? 1 : 0)) {
+    case 8: return launch_one(split_pass_kernel<ET, 4, false>, a, grid, block, lds, s);
+    case 9: return launch_one(split_pass_kernel<ET, 4, true>, a, grid, block, lds, s);
+    case 16: return launch_one(split_pass_kernel<ET, 8, false>, a, grid, block, lds, s);
+    case 17: return launch_one(split_pass_kernel<ET, 8, true>, a, grid, block, lds, s);
+    case 32: return launch_one(split_pass_kernel<ET, 16, false>, a, grid, block, lds, s);
+    case 33: return launch_one(split_pass_kernel<ET, 16, true>, a, grid, block, lds, s);
+    case 64: return launch_one(split_pass_kernel<ET, 32, false>, a, grid, block, lds, s);
+    case 65: return launch_one(split_pass_kernel<ET, 32, true>, a, grid, block, lds, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s) {
@@ -303,11 +470,12 @@ hipError_t launch_split_pass(const PassArgs& a, hipStream_t s) {
   if (a.nwaves != 2 && a.nwaves != 4 && a.nwaves != 8) return hipErrorInvalidValue;
   // per-lane input offsets are 32 bit: the rows of one step must lie within 2 GiB
   if (a.st * (int64_t)((a.nwaves / 2) * (kWave / lpr)) >= (1LL << 31)) return hipErrorInvalidValue;
-  const size_t lds = split_lds_bytes(a.D, a.L, a.k, a.nwaves);
-  if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
+  const bool ring = split_uses_ring(a.D, a.L, a.k, a.nwaves, lpr);
+  const size_t lds = (size_t)split_lds(a.D, a.L, a.k, a.nwaves, ring).total;
+  if (lds > kSplitMaxLds) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);
-  return a.esize == 4 ? launch_split_t<F32>(a, lpr, grid, block, lds, s)
-                      : launch_split_t<BF16>(a, lpr, grid, block, lds, s);
+  return a.esize == 4 ? launch_split_t<F32>(a, lpr, ring, grid, block, lds, s)
+                      : launch_split_t<BF16>(a, lpr, ring, grid, block, lds, s);
 }
 
 }  // namespace lagkv
