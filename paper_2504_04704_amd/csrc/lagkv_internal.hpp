@@ -53,7 +53,6 @@ bool fused_supported(int D, int esize, int64_t sb, int64_t sh, int64_t st, const
                      const void* V, const void* Ko, const void* Vo);
 size_t fused_lds_bytes(int D, int L, int k, int nwaves);
 
-
 // One-shot fused kernel (tensor-split streaming): nwaves in {2,4,8}.
 size_t split_lds_bytes(int D, int esize, int L, int k, int nwaves);
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s);

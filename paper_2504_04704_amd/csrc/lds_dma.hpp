@@ -1,0 +1,71 @@
+// Asynchronous global -> LDS row loads (gfx950 global_load_lds_dwordx4), the assembly
+// LDS accessors that go with them, and the streaming store used for output rows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "row_ops.hpp"
+
+#ifndef LAGKV_NT_STORE
+#define LAGKV_NT_STORE 1     // 1: non-temporal stores for the output rows (never re-read)
+#endif
+#ifndef LAGKV_SPLIT_RING
+#define LAGKV_SPLIT_RING 8   // 1 KiB LDS slots per wavefront for the asynchronous row loads
+#endif
+
+namespace lagkv {
+
+__device__ __forceinline__ void st16_out(char* p, const uint4& v) {
+#if LAGKV_NT_STORE
+  __builtin_nontemporal_store(v.x, reinterpret_cast<uint32_t*>(p));
+  __builtin_nontemporal_store(v.y, reinterpret_cast<uint32_t*>(p) + 1);
+  __builtin_nontemporal_store(v.z, reinterpret_cast<uint32_t*>(p) + 2);
+  __builtin_nontemporal_store(v.w, reinterpret_cast<uint32_t*>(p) + 3);
+#else
+  st16(p, v);
+#endif
+}
+
+// ---- asynchronous global -> LDS row loads (gfx950 global_load_lds_dwordx4) -----------
+// A wave-wide load writes lane l's 16 bytes to LDS at base + 16*l without passing
+// through VGPRs and is tracked by the vector-memory counter (vmcnt, in order).  Each
+// wavefront owns a ring of kRing slots of 1 KiB; a slot receives one step (64/LPR rows).
+// The loads are issued kRing-2 steps ahead of the arithmetic.  The LDS reads of landed
+// slots and the variance stores are written in assembly with explicit counter waits so
+// that they are not serialised behind the loads still in flight.
+constexpr int kRing = LAGKV_SPLIT_RING;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+// wait until at most PENDING vector-memory operations are outstanding, then read two
+// landed 16-byte entries
+template <int PENDING>
+__device__ __forceinline__ void lds_read_pair_after(u32x4& a, u32x4& b, uint32_t la, uint32_t lb) {
+  asm volatile(
+      "s_waitcnt vmcnt(%4)\n\t"
+      "ds_read_b128 %0, %2\n\t"
+      "ds_read_b128 %1, %3\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(a), "=&v"(b)
+      : "v"(la), "v"(lb), "n"(PENDING)
+      : "memory");
+}
+__device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
+  asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+
+// one landed LDS word (assembly: not ordered behind asynchronous loads in flight)
+__device__ __forceinline__ uint32_t lds_load_u32(uint32_t addr) {
+  uint32_t v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void vmem_drain() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+}  // namespace lagkv

@@ -68,9 +68,6 @@ __device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&
   for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
   s = group_sum<LPR>(s);
   const float mean = s * inv_D;
-#if defined(LAGKV_DIAG_SKIP_CENTRED)
-  return mean * inv_dof;  // diagnostic build only: skips the centred pass
-#endif
   float ss = 0.f;
 #pragma unroll
   for (int j = 0; j < VEC; ++j) {

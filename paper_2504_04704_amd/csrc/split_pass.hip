@@ -10,6 +10,7 @@
 // in flight (2 workgroups per CU x 2 x L rows) are sized to stay within the 256 MiB
 // memory-side cache, so that re-read does not go to HBM.
 #include "lagkv_internal.hpp"
+#include "lds_dma.hpp"
 #include "row_ops.hpp"
 #include "wave_ops.hpp"
 
@@ -19,12 +20,6 @@
 #ifndef LAGKV_SPLIT_UG
 #define LAGKV_SPLIT_UG 8     // kept rows in flight per lane in the compaction
 #endif
-#ifndef LAGKV_NT_STORE
-#define LAGKV_NT_STORE 1     // 1: non-temporal stores for the output rows (never re-read)
-#endif
-#ifndef LAGKV_SPLIT_RING
-#define LAGKV_SPLIT_RING 8   // 1 KiB LDS slots per wavefront for the asynchronous row loads
-#endif
 #ifndef LAGKV_SPLIT_DMA
 #define LAGKV_SPLIT_DMA 1    // 1: asynchronous global->LDS row loads when the rows of a chunk divide evenly
 #endif
@@ -33,50 +28,6 @@
 #endif
 
 namespace lagkv {
-
-__device__ __forceinline__ void st16_out(char* p, const uint4& v) {
-#if LAGKV_NT_STORE
-  __builtin_nontemporal_store(v.x, reinterpret_cast<uint32_t*>(p));
-  __builtin_nontemporal_store(v.y, reinterpret_cast<uint32_t*>(p) + 1);
-  __builtin_nontemporal_store(v.z, reinterpret_cast<uint32_t*>(p) + 2);
-  __builtin_nontemporal_store(v.w, reinterpret_cast<uint32_t*>(p) + 3);
-#else
-  st16(p, v);
-#endif
-}
-
-// ---- asynchronous global -> LDS row loads (gfx950 global_load_lds_dwordx4) -----------
-// A wave-wide load writes lane l's 16 bytes to LDS at base + 16*l without passing
-// through VGPRs and is tracked by the vector-memory counter (vmcnt, in order).  Each
-// wavefront owns a ring of kRing slots of 1 KiB; a slot receives one step (64/LPR rows).
-// The loads are issued kRing-2 steps ahead of the arithmetic.  The LDS reads of landed
-// slots and the variance stores are written in assembly with explicit counter waits so
-// that they are not serialised behind the loads still in flight.
-constexpr int kRing = LAGKV_SPLIT_RING;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-__device__ __forceinline__ uint32_t lds_offset(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
-}
-// wait until at most PENDING vector-memory operations are outstanding, then read two
-// landed 16-byte entries
-template <int PENDING>
-__device__ __forceinline__ void lds_read_pair_after(u32x4& a, u32x4& b, uint32_t la, uint32_t lb) {
-  asm volatile(
-      "s_waitcnt vmcnt(%4)\n\t"
-      "ds_read_b128 %0, %2\n\t"
-      "ds_read_b128 %1, %3\n\t"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&v"(a), "=&v"(b)
-      : "v"(la), "v"(lb), "n"(PENDING)
-      : "memory");
-}
-__device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
-  asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 struct SplitLds {
   int off_vK, off_vV, off_list, off_stat, off_ring, total;  // bytes
@@ -141,12 +92,6 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const bool local = a.variant == 1;  // Eq. 14-15: statistics from the chunk itself
 
   for (int i = tid; i < k; i += nthreads) list[i] = 0;
-#if defined(LAGKV_DIAG_DESYNC)
-  {  // diagnostic build only: start workgroups at different phases
-    const int d = (int)((blockIdx.x * 2654435761u) >> 29) * LAGKV_DIAG_DESYNC;
-    for (int i = 0; i < d; ++i) __builtin_amdgcn_s_sleep(127);
-  }
-#endif
 
   // sink rows and the sliding window (last full chunk + remainder) are plain copies
   if (gather && seg == 0 && S > 0) {
@@ -167,14 +112,6 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
 
   TStats<VEC> acc;
   TRef<VEC> ref;
-#if defined(LAGKV_DIAG_TIMING)
-  long long t_fold_pre = 0, t_fold_bar = 0, t_mark = wall_clock64();
-#define FOLD_TICK { const long long n_ = wall_clock64(); t_fold_pre += n_ - t_mark; t_mark = n_; }
-#define FOLD_TICK2 { const long long n_ = wall_clock64(); t_fold_bar += n_ - t_mark; t_mark = n_; }
-#else
-#define FOLD_TICK
-#define FOLD_TICK2
-#endif
 
   // One pass over the L rows of this wavefront's tensor.  When L is a multiple of the
   // rows one step covers (the usual case) a row address is a wave-uniform base plus one
@@ -313,9 +250,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
           w[a.D + j] = acc.mx[j];
         }
       }
-      FOLD_TICK
       __syncthreads();
-      FOLD_TICK2
       for (int g = 0; g < G; ++g) {
         const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
 #pragma unroll
@@ -376,43 +311,19 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   fold();
   ref.from(acc);
   __syncthreads();  // statbuf is rewritten by the next fold
-#if defined(LAGKV_DIAG_TIMING)
-  // diagnostic build only: per-phase cycle counts of wavefronts 0 and 1, written over the
-  // first entries of the workgroup's output index rows
-  long long t_scan = 0, t_fold = 0, t_sel = 0, t_wait = 0, t_comp = 0;
-#define TICK(acc_) { const long long now_ = wall_clock64(); acc_ += now_ - t_last; t_last = now_; }
-  long long t_last = wall_clock64();
-#else
-#define TICK(acc_)
-#endif
   for (int64_t p = p1 - 1; p >= p0; --p) {
     acc.reset();
     scan(S + p * L, T_{}, T_{});
-    TICK(t_scan)
-#if defined(LAGKV_DIAG_TIMING)
-    t_mark = t_last;
-#endif
     fold();  // barrier inside: the variances are visible
-    TICK(t_fold)
     if (wave == 0) {
       wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
     } else {
       ref.from(acc);  // chunk p is the reference of chunk p-1
     }
-    TICK(t_sel)
     __syncthreads();
-    TICK(t_wait)
     if (gather) compact(p);
     if (wave == 0) ref.from(acc);
-    TICK(t_comp)
   }
-#if defined(LAGKV_DIAG_TIMING)
-  if (iout && lane == 0) {
-    long long* d = reinterpret_cast<long long*>(iout + a.T_out - 256 + 16 * wave);  // inside the window part
-    d[0] = t_scan; d[1] = t_fold; d[2] = t_sel; d[3] = t_wait; d[4] = t_comp; d[5] = t_fold_pre; d[6] = t_fold_bar;
-  }
-#endif
-#undef TICK
 }
 
 // ------------------------------------------------------------------------ host side
