@@ -337,6 +337,192 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// Single-round decode step: the common call, in which the appended rows complete
+// exactly one more chunk (2L <= tail + new < 3L, sink already full, Eq. 7-11 scoring).
+// The new rows are never stored at the end of the tail first: the tail is addressed
+// "virtually" (row v lives in the cache when v < n_tail, else in K_new/V_new), every
+// row is read from memory once and written once at its final place:
+//   rows [L,2L)  reference chunk: min/max (Eq. 7-8), parked in LDS, stored at [k, k+L)
+//   rows [0,L)   scored (Eq. 9-11); the k kept rows are read again (L2) -> [0,k)
+//   rows [2L,..) -> [k+L, ..)
+// Half of the wavefronts handle K rows, half V rows (as in the one-shot kernel).
+// ---------------------------------------------------------------------------------
+struct StepLds {
+  int off_vK, off_vV, off_list, off_pos, off_stat, off_stash, total;  // bytes
+};
+__host__ __device__ inline StepLds step_lds(int D, int L, int k, int nw, int rowbytes) {
+  StepLds l;
+  const int lp = (L + 3) & ~3, kp = (k + 3) & ~3;
+  l.off_vK = 0;
+  l.off_vV = lp * 4;
+  l.off_list = 2 * lp * 4;
+  l.off_pos = l.off_list + kp * 4;               // positions of the (< 3L) tail rows
+  l.off_stat = l.off_pos + 3 * lp * 4;           // [wave][mn|mx][D]
+  l.off_stash = (l.off_stat + nw * 2 * D * 4 + 15) & ~15;  // [K|V][L][rowbytes]
+  l.total = l.off_stash + 2 * L * rowbytes;
+  return l;
+}
+
+template <typename ET, int LPR>
+__global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a) {
+  constexpr int VEC = ET::VEC, RPW = kWave / LPR, U = 4;
+  extern __shared__ float4 lds_raw[];
+  char* lds = reinterpret_cast<char*>(lds_raw);
+  const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nw = nthreads >> 6, G = nw >> 1;
+  constexpr int rowbytes = LPR * 16;
+  const int L = a.L, k = a.k;
+  const StepLds lay = step_lds(a.D, L, k, nw, rowbytes);
+  float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
+  float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
+  uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  int32_t* ptail = reinterpret_cast<int32_t*>(lds + lay.off_pos);
+  float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+
+  const int tensor = wave >= G ? 1 : 0;  // 0: K rows, 1: V rows
+  const int gslot = wave - tensor * G;
+  const int rl = lane / LPR, cl = lane % LPR;
+  const int R = G * RPW, row0 = gslot * RPW + rl;
+  const int n_iter = (L + R - 1) / R;
+  const int64_t stream = blockIdx.x;
+  const int64_t b = stream / a.H, h = stream % a.H;
+  // tail row 0 of this wavefront's tensor, at this lane's 16-byte slice
+  char* ct = (tensor ? a.V : a.K) + (stream * a.capacity + a.n_static) * rowbytes + cl * 16;
+  const char* fresh = a.n_new > 0 ? (tensor ? a.V_new : a.K_new) + b * a.nsb + h * a.nsh + cl * 16 : ct;
+  const int n_tail = (int)a.n_tail, n_all = (int)(a.n_tail + a.n_new);
+  auto src = [&](int v) -> const char* {
+    return v < n_tail ? ct + (int64_t)v * rowbytes : fresh + (int64_t)(v - n_tail) * a.nst;
+  };
+  float* myvar = tensor ? vV : vK;
+  char* mystash = lds + lay.off_stash + (size_t)tensor * L * rowbytes + cl * 16;
+  int32_t* pc = a.pos ? a.pos + stream * a.capacity + a.n_static : nullptr;
+  const float inv_D = 1.0f / (float)a.D;
+  const float inv_dof = 1.0f / (float)(a.D - a.ddof);
+
+  for (int i = tid; i < k; i += nthreads) list[i] = 0;
+  if (pc)
+    for (int v = tid; v < n_all; v += nthreads)
+      ptail[v] = v < n_tail ? pc[v] : (int32_t)(a.n_seen + (v - n_tail));
+
+  // 1. reference chunk (tail rows [L,2L)): statistics, rows parked in LDS
+  TStats<VEC> acc;
+  acc.reset();
+  for (int it = 0; it < n_iter; it += U) {
+    uint4 q[U];
+    int r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      r[u] = row0 + (it + u) * R;
+      q[u] = ld16(src(L + (r[u] < L ? r[u] : L - 1)));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[VEC];
+      unpack<ET>(q[u], x);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        acc.mn[j] = fminf(acc.mn[j], x[j]);
+        acc.mx[j] = fmaxf(acc.mx[j], x[j]);
+      }
+      if (r[u] < L) *reinterpret_cast<uint4*>(mystash + (size_t)r[u] * rowbytes) = q[u];
+    }
+  }
+#pragma unroll
+  for (int m = LPR; m < kWave; m <<= 1) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      acc.mn[j] = fminf(acc.mn[j], __shfl_xor(acc.mn[j], m));
+      acc.mx[j] = fmaxf(acc.mx[j], __shfl_xor(acc.mx[j], m));
+    }
+  }
+  if (rl == 0) {
+    float* w = statbuf + (size_t)wave * 2 * a.D + cl * VEC;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      w[j] = acc.mn[j];
+      w[a.D + j] = acc.mx[j];
+    }
+  }
+  __syncthreads();
+  for (int g = 0; g < G; ++g) {
+    const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      acc.mn[j] = fminf(acc.mn[j], rd[j]);
+      acc.mx[j] = fmaxf(acc.mx[j], rd[j + a.D]);
+    }
+  }
+  TRef<VEC> ref;
+  ref.from(acc);
+
+  // 2. the chunk (tail rows [0,L)): channel variance of every token (Eq. 9-10)
+  for (int it = 0; it < n_iter; it += U) {
+    uint4 q[U];
+    int r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      r[u] = row0 + (it + u) * R;
+      q[u] = ld16(src(r[u] < L ? r[u] : L - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[VEC];
+      unpack<ET>(q[u], x);
+      const float v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+      if (cl == 0 && r[u] < L) myvar[r[u]] = v;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) wave_score_select_lean(vK, vV, L, k, true, nullptr, list, nullptr, lane);
+  __syncthreads();
+
+  // 3. kept rows -> [0,k).  A batch is loaded, the workgroup synchronises, the batch is
+  // stored: destination <= source and later batches read rows above everything stored.
+  constexpr int UB = 4;
+  for (int s0 = 0; s0 < k; s0 += UB * R) {
+    uint4 g[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int s = s0 + u * R + row0;
+      if (s < k) g[u] = ld16(src((int)list[s]));
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int s = s0 + u * R + row0;
+      if (s < k) st16(ct + (int64_t)s * rowbytes, g[u]);
+    }
+  }
+  // 4. the parked reference rows -> [k, k+L): they cover dead rows of the chunk and their own
+  // old place only
+  for (int r = row0; r < L; r += R)
+    st16(ct + (int64_t)(k + r) * rowbytes, *reinterpret_cast<const uint4*>(mystash + (size_t)r * rowbytes));
+  // 5. the rest of the tail, rows [2L, n_all) -> [k+L, ..), batch by batch as in 3.
+  const int nrem = n_all - 2 * L;
+  for (int r0 = 0; r0 < nrem; r0 += UB * R) {
+    uint4 g[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int r = r0 + u * R + row0;
+      if (r < nrem) g[u] = ld16(src(2 * L + r));
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int r = r0 + u * R + row0;
+      if (r < nrem) st16(ct + (int64_t)(k + L + r) * rowbytes, g[u]);
+    }
+  }
+  if (pc) {  // every position was read into LDS before the first barrier
+    for (int s = tid; s < k; s += nthreads) pc[s] = ptail[list[s]];
+    for (int i = tid; i < n_all - L; i += nthreads) pc[k + i] = ptail[L + i];
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -363,6 +549,51 @@ static hipError_t launch_append_t(const AppendArgs& a, int lpr, dim3 grid, dim3 
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+// Largest LDS footprint of the single-round kernel: two workgroups share a CU.
+constexpr size_t kStepMaxLds = 80 * 1024;
+
+bool decode_step_supported(const AppendArgs& a) {
+  const int lpr = lanes_per_row(a.D, a.esize);
+  if (lpr == 0 || a.variant != 0 || a.rounds != 1 || a.n_seen < a.S) return false;
+  return (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total <= kStepMaxLds;
+}
+
+template <typename KF>
+static hipError_t launch_step_one(KF kernel, const AppendArgs& a, dim3 grid, dim3 block, size_t lds,
+                                  hipStream_t s) {
+  if (lds > 64 * 1024) {  // beyond the default dynamic LDS limit: opt in (idempotent)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  kernel<<<grid, block, lds, s>>>(a);
+  return hipGetLastError();
+}
+
+template <typename ET>
+static hipError_t launch_step_t(const AppendArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
+                                hipStream_t s) {
+  switch (lpr) {
+    case 4: return launch_step_one(decode_step_kernel<ET, 4>, a, grid, block, lds, s);
+    case 8: return launch_step_one(decode_step_kernel<ET, 8>, a, grid, block, lds, s);
+    case 16: return launch_step_one(decode_step_kernel<ET, 16>, a, grid, block, lds, s);
+    case 32: return launch_step_one(decode_step_kernel<ET, 32>, a, grid, block, lds, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_decode_step(const AppendArgs& a, hipStream_t s) {
+  const int lpr = lanes_per_row(a.D, a.esize);
+  const int64_t streams = (int64_t)a.B * a.H;
+  if (!decode_step_supported(a) || streams <= 0 || streams > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (a.n_tail + a.n_new < 2 * (int64_t)a.L || a.n_tail + a.n_new >= 3 * (int64_t)a.L)
+    return hipErrorInvalidValue;
+  const size_t lds = (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total;
+  const dim3 grid((unsigned)streams), block(8 * kWave);
+  return a.esize == 4 ? launch_step_t<F32>(a, lpr, grid, block, lds, s)
+                      : launch_step_t<BF16>(a, lpr, grid, block, lds, s);
 }
 
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s) {

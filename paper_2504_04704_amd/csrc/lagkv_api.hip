@@ -389,7 +389,9 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
       a.ddof = n.ddof;
       a.variant = n.variant;
       a.nwaves = pick_waves(n);
-      e = launch_fused_append(a, s);
+      // the single-round kernel serves the steady decode step unless a launch shape is forced
+      if (g_tune[LAGKV_TUNE_WAVES] == 0 && decode_step_supported(a)) e = launch_decode_step(a, s);
+      else e = launch_fused_append(a, s);
     }
   } else {
     if (!staged_fits(n)) return LAGKV_ESHAPE;

@@ -58,6 +58,9 @@ size_t split_lds_bytes(int D, int esize, int L, int k, int nwaves);
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s);
 
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s);
+// Single-round decode step (exactly one chunk completes; no intermediate append copy).
+bool decode_step_supported(const AppendArgs& a);
+hipError_t launch_decode_step(const AppendArgs& a, hipStream_t s);
 
 // Three-kernel path (any D, any alignment).
 hipError_t launch_staged_score(const PassArgs& a, int64_t row0, float* scores, hipStream_t s);

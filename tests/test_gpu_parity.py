@@ -258,6 +258,49 @@ def test_append_after_one_shot_equals_one_shot_on_history(path, dtype, D, varian
     oracle_history_check(cache, Kh, Vh, S, L, r, VARIANT_NAME[variant])
 
 
+@pytest.mark.parametrize("L,D,dtype,r", [(32, 128, torch.bfloat16, 0.25), (24, 64, torch.float32, 0.5),
+                                         (128, 128, torch.bfloat16, 0.25), (70, 32, torch.bfloat16, 0.1),
+                                         (16, 256, torch.bfloat16, 0.9), (50, 128, torch.float32, 0.33)])
+def test_single_round_decode_step_with_the_boundary_anywhere(L, D, dtype, r):
+    """The steady decode step (exactly one chunk completes) with the border between cached
+    and new rows inside the chunk, inside the reference, at their ends, and in the rest."""
+    S = 5
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
+    cases = [(0, 2 * L), (1, 3 * L - 2), (L - 1, L + 1), (L, L), (L + 1, L - 1), (L + L // 2, L // 2 + 3),
+             (2 * L - 1, 1), (2 * L - 1, L), (L + 3, 2 * L - 4)]
+    for n_tail, n_new in cases:
+        say("decode step", L, D, dtype, "tail", n_tail, "new", n_new)
+        T = S + n_tail + n_new
+        Kh, Vh = gen(2, 3, T, D, dtype, seed=L * 7 + n_tail)
+        cache = lagkv.Cache(2, 3, D, T + 4, S, L, r, dtype=dtype)
+        cache.append_and_compress(Kh[:, :, :S + n_tail], Vh[:, :, :S + n_tail])
+        assert cache.n_static == S and cache.n_tail == n_tail
+        cache.append_and_compress(Kh[:, :, S + n_tail:], Vh[:, :, S + n_tail:])
+        torch.cuda.synchronize()
+        assert cache.n_tail == n_tail + n_new - L
+        oracle_history_check(cache, Kh, Vh, S, L, r)
+
+
+def test_single_round_decode_step_repeats_and_without_positions():
+    S, L, r, D = 16, 128, 0.25, 128
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
+    T = S + 2 * L + 112 + 5 * L
+    Kh, Vh = gen(1, 4, T, D, torch.bfloat16, seed=99)
+    with_pos = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=True)
+    without = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=False)
+    t = 0
+    for n in [S + L + 112] + [L] * 6:
+        say("decode steps", t, n)
+        with_pos.append_and_compress(Kh[:, :, t:t + n], Vh[:, :, t:t + n])
+        without.append_and_compress(Kh[:, :, t:t + n], Vh[:, :, t:t + n])
+        t += n
+    torch.cuda.synchronize()
+    oracle_history_check(with_pos, Kh, Vh, S, L, r)
+    n = with_pos.length
+    assert without.length == n
+    assert torch.equal(without.K[:, :, :n], with_pos.K[:, :, :n]) and torch.equal(without.V[:, :, :n], with_pos.V[:, :, :n])
+
+
 def test_append_capacity_error_leaves_cache_untouched():
     cache = lagkv.Cache(1, 1, 128, 64, 4, 16, 0.5)
     Kn, Vn = gen(1, 1, 65, 128, torch.bfloat16, seed=81)
@@ -287,19 +330,19 @@ def _full_config(name, n_sample, want_scores=True):
 
 
 def test_config2_llama8b_16k():
-    out, _ = _full_config("cfg2_llama8b_16k", 24)
+    out, _ = _full_config("cfg2_llama8b_16k", 256)  # every stream
     assert out.plan.T_out == 4288
 
 
 def test_config3_llama8b_64k():
-    out, _ = _full_config("cfg3_llama8b_64k", 8)
+    out, _ = _full_config("cfg3_llama8b_64k", 64)
     assert out.plan.T_out == 8640
 
 
 def test_config4_llama8b_128k_b4_bench_configuration():
     """The headline workload in the launch configuration bench.py times (defaults,
     no score dump): 64 GiB scanned, sampled streams against the oracle."""
-    out, _ = _full_config("cfg4_llama8b_128k_b4", 6, want_scores=False)
+    out, _ = _full_config("cfg4_llama8b_128k_b4", 32, want_scores=False)
     assert out.plan.T_out == 33536
 
 
