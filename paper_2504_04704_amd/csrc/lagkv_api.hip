@@ -105,22 +105,27 @@ bool staged_fits(const Norm& n) {
 }
 
 // Wavefronts per workgroup of the tensor-split kernel (0 = its LDS need does not fit).
+// Long chunks keep eight wavefronts streaming; for short chunks the per-chunk serial part
+// (fold, selection by one wavefront, barriers) weighs more, and smaller workgroups - more of
+// them per CU, each with its own selection - overlap it better (measured: L=128 0.59 ms with 2
+// against 0.80 ms with 8 wavefronts on 256 streams of 16K rows).
 int split_nw(const Norm& n) {
-  int nw = 8;
+  int nw = n.L >= 512 ? 8 : n.L >= 256 ? 4 : 2;
   const int64_t t = g_tune[LAGKV_TUNE_WAVES];
   if (t == 2 || t == 4 || t == 8) nw = (int)t;
   while (nw >= 2 && split_lds_bytes(n.D, n.esize, n.L, n.k, nw) > (size_t)80 * 1024) nw >>= 1;
   return nw >= 2 ? nw : 0;
 }
 
-// 16 wavefronts fit a CU: cut streams into segments only until every CU of the chip
-// (256) is covered twice, and keep segments >= 4 chunks.
+// Streams are cut into segments only when there are too few of them to fill the chip: the
+// target is 2 workgroups per CU (256 CUs) of 8 wavefronts, 3 of 4, 4 of 2 (measured optima;
+// every segment reads one extra chunk for its first reference), and segments keep >= 4 chunks.
 int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   int64_t nseg;
   if (g_tune[LAGKV_TUNE_SEGMENTS]) {
     nseg = g_tune[LAGKV_TUNE_SEGMENTS];
   } else {
-    const int64_t capacity = 2 * 256 * (16 / nw);
+    const int64_t capacity = 256 * (nw >= 8 ? 2 : nw >= 4 ? 3 : 4);
     nseg = n.streams >= capacity ? 1 : (capacity + n.streams - 1) / n.streams;
     const int64_t cap = n_s / 4 > 1 ? n_s / 4 : 1;
     if (nseg > cap) nseg = cap;

@@ -315,14 +315,12 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     acc.reset();
     scan(S + p * L, T_{}, T_{});
     fold();  // barrier inside: the variances are visible
-    if (wave == 0) {
+    ref.from(acc);  // chunk p is the reference of chunk p-1 (done before the selection so
+                    // that the running statistics are dead across it: fewer live registers)
+    if (wave == 0)
       wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
-    } else {
-      ref.from(acc);  // chunk p is the reference of chunk p-1
-    }
     __syncthreads();
     if (gather) compact(p);
-    if (wave == 0) ref.from(acc);
   }
 }
 

@@ -73,10 +73,12 @@ SHAPES = [
     (1, 1, 16 + 2 * 1024 + 5, 128, torch.bfloat16, 16, 1024, 0.125),
     (1, 1, 2 + 2 * 1500 + 1, 64, torch.float32, 2, 1500, 0.01),      # L > 1024: LDS-resident keys
     (3, 2, 1 + 9 * 3, 16, torch.float32, 1, 3, 0.67),                # tiny L
+    (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.02),        # k = 1
+    (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.99),        # k = L - 1
 ]
 
 
-@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}T{s[2]}D{s[3]}{'f32' if s[4] == torch.float32 else 'bf16'}S{s[5]}L{s[6]}")
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}T{s[2]}D{s[3]}{'f32' if s[4] == torch.float32 else 'bf16'}S{s[5]}L{s[6]}r{s[7]}")
 @pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
 def test_shapes_against_oracle(shape, path):
     B, H, T, D, dtype, S, L, r = shape
