@@ -227,7 +227,8 @@ def bench_decode(args):
         "roofline": {"bound": "hbm", "achieved": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "decode_step_kernel", "algorithmic_bytes": alg},
+                     "traffic": read_traffic("decode_step_cfg5_decode_b32.md") if cfg.B == 32 else None,
+                     "kernel": "decode_step_kernel", "algorithmic_bytes": alg},
     }
 
 
