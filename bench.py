@@ -119,8 +119,12 @@ def bench_compress(args):
     Vo = torch.empty_like(Ko)
     idx = torch.empty((Bf, H, pl.T_out), dtype=torch.int32, device=dev)
 
+    # caller-owned workspace (only the three-kernel path uses it): nothing is allocated per step
+    nws = lagkv.workspace_bytes(p, cfg.T)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+
     def step():
-        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, out=(Ko, Vo), idx_out=idx)
+        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, out=(Ko, Vo), idx_out=idx, ws=ws)
 
     for _ in range(args.warmup):
         step()
