@@ -24,7 +24,7 @@
  *   - The library allocates no device memory and keeps no per-call state.
  *   - Return value: a lagkv_status.  Inputs must be finite; NaN/Inf give
  *     unspecified scores (never out-of-bounds accesses).
- *   - Arithmetic: inputs as stored (fp32 or bf16), all scoring math in fp32,
+ *   - Arithmetic: inputs as stored (fp32, bf16 or fp16), all scoring math in fp32,
  *     scores fp32, kept rows copied bit for bit.
  */
 #ifndef LAGKV_H
@@ -47,7 +47,7 @@ typedef enum {
   LAGKV_EHIP = 6        /* a HIP runtime call or kernel launch failed                            */
 } lagkv_status;
 
-typedef enum { LAGKV_F32 = 0, LAGKV_BF16 = 1 } lagkv_dtype;
+typedef enum { LAGKV_F32 = 0, LAGKV_BF16 = 1, LAGKV_F16 = 2 /* IEEE binary16 */ } lagkv_dtype;
 
 typedef enum {
   LAGKV_SCORE_LAG = 0,   /* Eq. 7-11: min/max from the next chunk                       */
@@ -82,6 +82,19 @@ typedef struct {
  * no-op ("skip the compression"): n_scored = 0 and T_out = T; not an error.
  */
 int lagkv_plan(const lagkv_params* p, int64_t T, int64_t n_static, lagkv_plan_t* out);
+
+/*
+ * Inverse of Eq. 12-13 (host only): the retention that reaches a wanted compression
+ * ratio C = 1 - L_R / T at fixed sink S and lag L, as the Experiments section does when
+ * it adapts r per target ratio.  *k_out receives the LARGEST k in [1, L] whose
+ * compression ratio (Eq. 13 with rL = k) is >= C, i.e. the most rows that may be kept
+ * per chunk while still compressing at least that much; *r_out a ratio with
+ * floor(r * L) == k exactly (the midpoint (k + 0.5) / L, or 1 when k == L).
+ * LAGKV_EINVAL: null pointers, S < 0, L < 1, T < S + 2L (nothing is compressed, C = 0
+ * whatever r), C outside [0, 1), or C not reachable even with k = 1.
+ */
+int lagkv_keep_for_compression(int64_t T, int32_t S, int32_t L, double C, int64_t* k_out,
+                               double* r_out);
 
 /*
  * Device workspace, in bytes, that lagkv_score / lagkv_compress /

@@ -87,6 +87,18 @@ def compression_ratio(Ls: int, S: int, L: int, rL: int) -> float:
     return 1.0 - eq12_length(Ls, S, L, rL) / Ls
 
 
+def keep_for_compression(Ls: int, S: int, L: int, C: float) -> int:
+    """Inverse of Eq. 13 by exhaustion: the largest rL in [1, L] whose compression
+    ratio is at least C (the Experiments section adapts r to a target ratio at fixed
+    L this way).  Raises when Ls < S + 2L or when even rL = 1 compresses less than C."""
+    if Ls < S + 2 * L or not (0.0 <= C < 1.0):
+        raise ValueError("no compression ratio to reach")
+    for rL in range(L, 0, -1):
+        if compression_ratio(Ls, S, L, rL) >= C:
+            return rL
+    raise ValueError("C is not reachable with rL >= 1")
+
+
 # --------------------------------------------------------------------------
 # scoring one chunk (Eq. 7-11)
 # --------------------------------------------------------------------------

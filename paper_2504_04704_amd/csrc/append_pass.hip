@@ -592,8 +592,9 @@ hipError_t launch_decode_step(const AppendArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   const size_t lds = (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total;
   const dim3 grid((unsigned)streams), block(8 * kWave);
-  return a.esize == 4 ? launch_step_t<F32>(a, lpr, grid, block, lds, s)
-                      : launch_step_t<BF16>(a, lpr, grid, block, lds, s);
+  if (a.esize == 4) return launch_step_t<F32>(a, lpr, grid, block, lds, s);
+  return a.f16 ? launch_step_t<F16>(a, lpr, grid, block, lds, s)
+               : launch_step_t<BF16>(a, lpr, grid, block, lds, s);
 }
 
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s) {
@@ -603,8 +604,9 @@ hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s) {
   const size_t lds = fused_lds_bytes(a.D, a.L, a.k, a.nwaves);
   if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;
   const dim3 grid((unsigned)streams), block(a.nwaves * kWave);
-  return a.esize == 4 ? launch_append_t<F32>(a, lpr, grid, block, lds, s)
-                      : launch_append_t<BF16>(a, lpr, grid, block, lds, s);
+  if (a.esize == 4) return launch_append_t<F32>(a, lpr, grid, block, lds, s);
+  return a.f16 ? launch_append_t<F16>(a, lpr, grid, block, lds, s)
+               : launch_append_t<BF16>(a, lpr, grid, block, lds, s);
 }
 
 }  // namespace lagkv

@@ -19,14 +19,14 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Norm {  // validated, normalised parameters
-  int B, H, D, S, L, k, esize, ddof, variant;
+  int B, H, D, S, L, k, esize, f16, ddof, variant;
   int64_t streams;
   int64_t rowbytes;
 };
 
 int validate(const lagkv_params* p, Norm* n) {
   if (!p) return LAGKV_EINVAL;
-  if (p->dtype != LAGKV_F32 && p->dtype != LAGKV_BF16) return LAGKV_EDTYPE;
+  if (p->dtype != LAGKV_F32 && p->dtype != LAGKV_BF16 && p->dtype != LAGKV_F16) return LAGKV_EDTYPE;
   if (p->variant < LAGKV_SCORE_LAG || p->variant > LAGKV_SCORE_L2) return LAGKV_EDTYPE;
   if (p->reserved != 0) return LAGKV_EINVAL;
   if (p->std_ddof != 0 && p->std_ddof != 1) return LAGKV_EINVAL;
@@ -44,6 +44,7 @@ int validate(const lagkv_params* p, Norm* n) {
   n->L = p->L;
   n->k = (int)kd;
   n->esize = p->dtype == LAGKV_F32 ? 4 : 2;
+  n->f16 = p->dtype == LAGKV_F16 ? 1 : 0;
   n->ddof = p->std_ddof;
   n->variant = p->variant;
   n->streams = (int64_t)p->B * p->H;
@@ -198,6 +199,7 @@ void fill_pass(PassArgs* a, const Norm& n, const void* K, const void* V, int64_t
   a->L = n.L;
   a->k = n.k;
   a->esize = n.esize;
+  a->f16 = n.f16;
   a->ddof = n.ddof;
   a->variant = n.variant;
   a->nseg = 1;
@@ -217,6 +219,25 @@ int lagkv_plan(const lagkv_params* p, int64_t T, int64_t n_static, lagkv_plan_t*
   if (n_static < 0) n_static = n.S;
   if (n_static > T && T >= n.S) return LAGKV_EINVAL;
   plan_of(n, T, n_static, out);
+  return LAGKV_OK;
+}
+
+int lagkv_keep_for_compression(int64_t T, int32_t S, int32_t L, double C, int64_t* k_out,
+                               double* r_out) {
+  if (!k_out || !r_out || S < 0 || L < 1 || !(C >= 0.0) || !(C < 1.0)) return LAGKV_EINVAL;
+  if (T < (int64_t)S + 2 * (int64_t)L) return LAGKV_EINVAL;
+  const int64_t n_s = (T - S) / L - 1, m = (T - S) % L;
+  // Eq. 12-13 with rL = k: C(k) = 1 - (S + k*n_s + L + m) / T, decreasing in k.  Start from the
+  // closed form and settle the boundary with the exact comparison the definition uses.
+  auto ratio = [&](int64_t k) { return 1.0 - (double)(S + k * n_s + L + m) / (double)T; };
+  int64_t k = (int64_t)std::floor(((1.0 - C) * (double)T - (double)(S + L + m)) / (double)n_s);
+  if (k > L) k = L;
+  if (k < 1) k = 1;
+  while (k < L && ratio(k + 1) >= C) ++k;
+  while (k >= 1 && ratio(k) < C) --k;
+  if (k < 1) return LAGKV_EINVAL;
+  *k_out = k;
+  *r_out = k == L ? 1.0 : ((double)k + 0.5) / (double)L;
   return LAGKV_OK;
 }
 
@@ -391,6 +412,7 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
       a.L = n.L;
       a.k = n.k;
       a.esize = n.esize;
+      a.f16 = n.f16;
       a.ddof = n.ddof;
       a.variant = n.variant;
       a.nwaves = pick_waves(n);

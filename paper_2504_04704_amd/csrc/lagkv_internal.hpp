@@ -21,7 +21,8 @@ struct PassArgs {
   int64_t n_s;         // scored chunks per stream (>= 1)
   int32_t B, H, D;
   int32_t S, L, k;
-  int32_t esize;       // bytes per element (4 = fp32, 2 = bf16)
+  int32_t esize;       // bytes per element (4 = fp32, 2 = bf16 or fp16)
+  int32_t f16;         // 2-byte elements are IEEE binary16 (else bfloat16)
   int32_t ddof;
   int32_t variant;
   int32_t nseg;        // segments per stream (fused kernel)
@@ -44,7 +45,7 @@ struct AppendArgs {
   int64_t rounds;      // chunks to compress after the append (host arithmetic)
   int32_t B, H, D;
   int32_t S, L, k;
-  int32_t esize, ddof, variant;
+  int32_t esize, f16, ddof, variant;
   int32_t nwaves;
 };
 

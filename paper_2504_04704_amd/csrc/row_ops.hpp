@@ -8,20 +8,36 @@
 
 namespace lagkv {
 
+// Element types: VEC = elements in 16 bytes.
 struct F32 {
   static constexpr int VEC = 4;
+  static constexpr int KIND = 0;
 };
 struct BF16 {
   static constexpr int VEC = 8;
+  static constexpr int KIND = 1;
 };
+struct F16 {
+  static constexpr int VEC = 8;
+  static constexpr int KIND = 2;
+};
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 template <typename ET>
 __device__ __forceinline__ void unpack(const uint4& q, float (&x)[ET::VEC]) {
-  if constexpr (ET::VEC == 4) {
+  if constexpr (ET::KIND == 0) {
     x[0] = __uint_as_float(q.x);
     x[1] = __uint_as_float(q.y);
     x[2] = __uint_as_float(q.z);
     x[3] = __uint_as_float(q.w);
+  } else if constexpr (ET::KIND == 2) {  // binary16 -> fp32 is exact (hardware conversion)
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+      x[2 * i] = (float)h.x;
+      x[2 * i + 1] = (float)h.y;
+    }
   } else {  // bf16 -> fp32 is a 16-bit shift; element 2i is the low half of word i
     x[0] = __uint_as_float(q.x << 16);
     x[1] = __uint_as_float(q.x & 0xffff0000u);

@@ -383,8 +383,9 @@ hipError_t launch_split_pass(const PassArgs& a, hipStream_t s) {
   const size_t lds = (size_t)split_lds(a.D, a.L, a.k, a.nwaves, ring).total;
   if (lds > kSplitMaxLds) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nblocks), block(a.nwaves * kWave);
-  return a.esize == 4 ? launch_split_t<F32>(a, lpr, ring, grid, block, lds, s)
-                      : launch_split_t<BF16>(a, lpr, ring, grid, block, lds, s);
+  if (a.esize == 4) return launch_split_t<F32>(a, lpr, ring, grid, block, lds, s);
+  return a.f16 ? launch_split_t<F16>(a, lpr, ring, grid, block, lds, s)
+               : launch_split_t<BF16>(a, lpr, ring, grid, block, lds, s);
 }
 
 }  // namespace lagkv

@@ -9,8 +9,10 @@
 
 namespace lagkv {
 
-__device__ __forceinline__ float load_elem(const char* row, int c, int esize) {
-  if (esize == 4) return reinterpret_cast<const float*>(row)[c];
+// ekind: 4 = fp32, 2 = bf16, 3 = fp16
+__device__ __forceinline__ float load_elem(const char* row, int c, int ekind) {
+  if (ekind == 4) return reinterpret_cast<const float*>(row)[c];
+  if (ekind == 3) return (float)reinterpret_cast<const _Float16*>(row)[c];
   return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(row)[c] << 16);
 }
 
@@ -23,7 +25,7 @@ __global__ void __launch_bounds__(256) staged_score_kernel(const PassArgs a, int
                                                            float* __restrict__ scores) {
   extern __shared__ float4 lds_raw[];
   float* lds = reinterpret_cast<float*>(lds_raw);
-  const int D = a.D, L = a.L, esize = a.esize;
+  const int D = a.D, L = a.L, esize = a.esize == 4 ? 4 : (a.f16 ? 3 : 2);
   float* mnK = lds;
   float* ivK = mnK + D;
   float* mnV = ivK + D;

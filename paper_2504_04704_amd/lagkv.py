@@ -19,13 +19,14 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblagkv.s
 _lib = None
 
 OK, EINVAL, ESHAPE, EDTYPE, ECAPACITY, EWORKSPACE, EHIP = range(7)
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 SCORE_LAG, SCORE_LOCAL, SCORE_L2 = 0, 1, 2
 TUNE_PATH, TUNE_WAVES, TUNE_SEGMENTS = 0, 1, 2
 PATH_AUTO, PATH_FUSED, PATH_STAGED = 0, 1, 2
 
-EXPORTS = ("lagkv_plan", "lagkv_workspace_bytes", "lagkv_score", "lagkv_select", "lagkv_compress",
-           "lagkv_append_and_compress", "lagkv_tune", "lagkv_strerror", "lagkv_version")
+EXPORTS = ("lagkv_plan", "lagkv_keep_for_compression", "lagkv_workspace_bytes", "lagkv_score",
+           "lagkv_select", "lagkv_compress", "lagkv_append_and_compress", "lagkv_tune",
+           "lagkv_strerror", "lagkv_version")
 
 
 class LagKVError(RuntimeError):
@@ -70,6 +71,9 @@ def load():
     vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
     lib.lagkv_plan.argtypes = [C.POINTER(Params), i64, i64, C.POINTER(PlanT)]
     lib.lagkv_plan.restype = C.c_int
+    lib.lagkv_keep_for_compression.argtypes = [i64, C.c_int32, C.c_int32, C.c_double,
+                                               C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.lagkv_keep_for_compression.restype = C.c_int
     lib.lagkv_workspace_bytes.argtypes = [C.POINTER(Params), i64]
     lib.lagkv_workspace_bytes.restype = sz
     lib.lagkv_score.argtypes = [C.POINTER(Params), vp, vp, i64, vp, vp, sz, vp]
@@ -104,7 +108,7 @@ def _check(status: int, where: str):
         raise LagKVError(status, where)
 
 
-_DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
 
 def make_params(B: int, H: int, D: int, S: int, L: int, r: float, dtype=BF16, variant=SCORE_LAG,
@@ -129,6 +133,14 @@ def plan(p: Params, T: int, n_static: int = -1) -> PlanT:
     out = PlanT()
     _check(load().lagkv_plan(C.byref(p), T, n_static, C.byref(out)), "lagkv_plan")
     return out
+
+
+def keep_for_compression(T: int, S: int, L: int, ratio: float) -> Tuple[int, float]:
+    """lagkv_keep_for_compression: (k, r) reaching compression ratio >= `ratio` at fixed S, L."""
+    k, r = C.c_int64(), C.c_double()
+    _check(load().lagkv_keep_for_compression(T, S, L, ratio, C.byref(k), C.byref(r)),
+           "lagkv_keep_for_compression")
+    return int(k.value), float(r.value)
 
 
 def workspace_bytes(p: Params, T: int) -> int:
@@ -304,6 +316,26 @@ class Cache:
             C.byref(p), C.byref(self.c), _ptr(K_new), _ptr(V_new), n_new, _ptr(self._ws),
             0 if self._ws is None else self._ws.numel(), _stream_ptr(self.K.device)),
             "lagkv_append_and_compress")
+
+
+    def prefill_chunked(self, K: torch.Tensor, V: torch.Tensor) -> int:
+        """Chunk-by-chunk compression during prefill (Ablation, "Chunk-by-Chunk Compression in
+        Prefill Stage"): the first S + 2L rows in one call, then L rows per call until all rows
+        are in; every call is lagkv_append_and_compress.  The model forward that would produce
+        each slice between the calls is the caller's; here the rows are given.  Returns the
+        number of calls made."""
+        T = K.shape[2]
+        first = min(T, self.S + 2 * self.L) if self.n_seen == 0 else 0
+        calls, t = 0, 0
+        if first:
+            self.append_and_compress(K[:, :, :first], V[:, :, :first])
+            calls, t = 1, first
+        while t < T:
+            n = min(self.L, T - t)
+            self.append_and_compress(K[:, :, t:t + n], V[:, :, t:t + n])
+            t += n
+            calls += 1
+        return calls
 
     def view(self) -> Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
         n = self.length

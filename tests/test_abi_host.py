@@ -86,6 +86,32 @@ def _status(fn, *a):
     return lagkv.OK
 
 
+def test_keep_for_compression_matches_the_exhaustive_oracle(lib):
+    """lagkv_keep_for_compression (closed form + boundary fix-up) against the oracle's
+    exhaustive search over rL, on a random grid and at its error cases."""
+    import random
+    from paper_2504_04704_amd import lagkv
+    rnd = random.Random(11)
+    for _ in range(2000):
+        L = rnd.randint(1, 300); S = rnd.randint(0, 64)
+        T = S + 2 * L + rnd.randint(0, 80 * L)
+        target = rnd.choice([0.0, rnd.random() * 0.999, O.compression_ratio(T, S, L, rnd.randint(1, L))])
+        target = min(max(target, 0.0), 0.999)
+        try:
+            want = O.keep_for_compression(T, S, L, target)
+        except ValueError:
+            with pytest.raises(lagkv.LagKVError):
+                lagkv.keep_for_compression(T, S, L, target)
+            continue
+        k, r = lagkv.keep_for_compression(T, S, L, target)
+        assert k == want, (T, S, L, target)
+        assert O.keep_count(L, r) == k and 0 < r <= 1
+    for bad in [(100, 16, 128, 0.5), (10**6, 16, 128, 1.0), (10**6, 16, 128, -0.1), (10**6, -1, 128, 0.5),
+                (10**6, 16, 0, 0.5), (10**6, 16, 128, float("nan"))]:
+        with pytest.raises(lagkv.LagKVError):
+            lagkv.keep_for_compression(*bad)
+
+
 def test_parameter_validation(lib):
     ok = dict(B=1, H=2, D=64, S=16, L=128, r=0.5)
     def P(**kw):

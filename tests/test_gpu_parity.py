@@ -31,8 +31,11 @@ def _reset_tuning():
 
 def gen(B, H, T, D, dtype, seed, device=DEV):
     cfg = synth.KVConfig("t", layers=1, B=B, H=H, D=D, T=T, S=0, L=1, r=1.0,
-                         dtype="f32" if dtype == torch.float32 else "bf16", n_outlier=min(2, D // 8))
-    return synth.make_kv(cfg, device=device, seed=seed)
+                         dtype="bf16" if dtype == torch.bfloat16 else "f32", n_outlier=min(2, D // 8))
+    K, V = synth.make_kv(cfg, device=device, seed=seed)
+    if dtype == torch.float16:   # generated in fp32, rounded to binary16 (values are O(10): in range)
+        K, V = K.to(torch.float16), V.to(torch.float16)
+    return K, V
 
 
 def run_and_check(K, V, S, L, r, variant=lagkv.SCORE_LAG, ddof=1, streams=None):
@@ -75,10 +78,12 @@ SHAPES = [
     (3, 2, 1 + 9 * 3, 16, torch.float32, 1, 3, 0.67),                # tiny L
     (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.02),        # k = 1
     (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.99),        # k = L - 1
+    (2, 2, 16 + 4 * 128 + 50, 128, torch.float16, 16, 128, 0.25),    # fp16, ring path
+    (1, 2, 7 + 5 * 100 + 3, 64, torch.float16, 7, 100, 0.167),       # fp16, register path, r*L = 16.7
 ]
 
 
-@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}T{s[2]}D{s[3]}{'f32' if s[4] == torch.float32 else 'bf16'}S{s[5]}L{s[6]}r{s[7]}")
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}T{s[2]}D{s[3]}{str(s[4]).split('.')[-1]}S{s[5]}L{s[6]}r{s[7]}")
 @pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
 def test_shapes_against_oracle(shape, path):
     B, H, T, D, dtype, S, L, r = shape
@@ -90,7 +95,8 @@ def test_shapes_against_oracle(shape, path):
     say("ok: chunks", rep.chunks, "flipped", rep.flipped_chunks, "max rel", rep.max_score_rel)
 
 
-@pytest.mark.parametrize("D,dtype", [(40, torch.float32), (96, torch.bfloat16), (5, torch.float32), (300, torch.bfloat16)])
+@pytest.mark.parametrize("D,dtype", [(40, torch.float32), (96, torch.bfloat16), (5, torch.float32), (300, torch.bfloat16),
+                                     (72, torch.float16)])
 def test_unaligned_head_dims_use_the_staged_path(D, dtype):
     say("unaligned D", D, dtype)
     K, V = gen(1, 2, 8 + 4 * 50 + 7, D, dtype, seed=D)
@@ -301,6 +307,20 @@ def test_single_round_decode_step_repeats_and_without_positions():
     n = with_pos.length
     assert without.length == n
     assert torch.equal(without.K[:, :, :n], with_pos.K[:, :, :n]) and torch.equal(without.V[:, :, :n], with_pos.V[:, :, :n])
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_prefill_chunk_by_chunk_equals_one_shot(dtype):
+    """S + 2L rows first, then L rows per call (the chunked prefill of the ablation)."""
+    S, L, r, D = 16, 64, 0.25, 128
+    T = S + 2 * L + 7 * L + 13
+    Kh, Vh = gen(2, 2, T, D, dtype, seed=123)
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
+    cache = lagkv.Cache(2, 2, D, T, S, L, r, dtype=dtype)
+    calls = cache.prefill_chunked(Kh, Vh)
+    torch.cuda.synchronize()
+    assert calls == 1 + 8
+    oracle_history_check(cache, Kh, Vh, S, L, r)
 
 
 def test_append_capacity_error_leaves_cache_untouched():

@@ -308,3 +308,34 @@ def test_gather_from_raw_arrays():
     rawK = np.arange(100, dtype=np.uint16); rawV = rawK + 1000
     Ko, Vo, idx, _ = O.compress(K, V, 2, 10, 0.5, raw=(rawK, rawV))
     assert np.array_equal(Ko, idx.astype(np.uint16)) and np.array_equal(Vo, Ko + 1000)
+
+
+# ---------------------------------------------------------------- inverse of Eq. 13
+def test_keep_for_compression_inverts_eq13():
+    """Round trip through the printed formula: the ratio of Eq. 13 at rL = k0 is reached
+    with exactly k0; anything above it needs fewer rows; the answer is the boundary of
+    the definition (C(k) >= C > C(k+1)); a long sequence approaches 1 - r."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        L = int(rng.integers(1, 200)); S = int(rng.integers(0, 40))
+        T = S + 2 * L + int(rng.integers(0, 50 * L))
+        k0 = int(rng.integers(1, L + 1))
+        c0 = O.compression_ratio(T, S, L, k0)
+        if c0 < 0:
+            continue
+        assert O.keep_for_compression(T, S, L, c0) == k0 or (T - S) // L - 1 == 0
+        k = O.keep_for_compression(T, S, L, max(c0 - 1e-9, 0.0))
+        assert O.compression_ratio(T, S, L, k) >= max(c0 - 1e-9, 0.0)
+        assert k == L or O.compression_ratio(T, S, L, k + 1) < max(c0 - 1e-9, 0.0)
+        if k0 > 1:
+            c_up = 0.5 * (c0 + O.compression_ratio(T, S, L, k0 - 1))
+            assert O.keep_for_compression(T, S, L, c_up) == k0 - 1
+    # the Experiments grid: 2x, 4x, 8x of a long cache at L = 128 keep ~ r*L rows per chunk
+    T = 16 + 128 * 100000
+    for times, rL in ((2, 64), (4, 32), (8, 16)):
+        assert O.keep_for_compression(T, 16, 128, 1.0 - 1.0 / times - 1e-4) == rL
+    assert O.keep_for_compression(T, 16, 128, 0.0) == 128
+    with pytest.raises(ValueError):
+        O.keep_for_compression(16 + 255, 16, 128, 0.1)            # shorter than S + 2L: C is 0
+    with pytest.raises(ValueError):
+        O.keep_for_compression(T, 16, 128, 0.9999)                # below one row per chunk
