@@ -112,7 +112,7 @@ def bench_compress(args):
     torch.cuda.synchronize()
     print(f"[bench] generated {cfg.name}: {2 * K.numel() * K.element_size() / 2**30:.1f} GiB in "
           f"{time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
-    p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r)
+    p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r, variant={"lag": 0, "local": 1, "l2": 2}[args.variant])
     pl = lagkv.plan(p, cfg.T)
     Bf, H, T, D = K.shape
     Ko = torch.empty((Bf, H, pl.T_out, D), dtype=K.dtype, device=dev)
@@ -123,8 +123,10 @@ def bench_compress(args):
     nws = lagkv.workspace_bytes(p, cfg.T)
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
 
+    variant = {"lag": lagkv.SCORE_LAG, "local": lagkv.SCORE_LOCAL, "l2": lagkv.SCORE_L2}[args.variant]
+
     def step():
-        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, out=(Ko, Vo), idx_out=idx, ws=ws)
+        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, ws=ws)
 
     for _ in range(args.warmup):
         step()
@@ -143,8 +145,13 @@ def bench_compress(args):
     ms_per_step = wall * 1e3 / args.steps
     tokens = cfg.B * cfg.T                      # one token = one (batch, position) over all layers and heads
     alg = algorithmic_bytes(cfg.streams, cfg.T, pl.T_out, cfg.D, K.element_size())
+    kernel = "split_pass_kernel"
+    if args.variant == "l2":
+        # Eq. 16 scores from K alone: V is read only where it is kept
+        alg = cfg.streams * (K.element_size() * cfg.D * (cfg.T + 3 * pl.T_out) + 4 * pl.T_out)
+        kernel = "staged_score_kernel + select_kernel + gather_rows_kernel x2"
     achieved = alg / (kern_avg_ms * 1e-3) / 1e9
-    traffic = read_traffic(f"split_pass_{cfg.name}_traffic.txt")
+    traffic = read_traffic(f"split_pass_{cfg.name}_traffic.txt") if args.variant == "lag" else None
     res = {
         "metric": "kv_tokens_compressed_per_sec_128k_ctx" if cfg.T == 131072 else "kv_tokens_compressed_per_sec",
         "value": tokens / (ms_per_step * 1e-3),
@@ -154,15 +161,15 @@ def bench_compress(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "B": cfg.B, "H_kv": cfg.H, "D": cfg.D,
-                   "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype,
+                   "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype, "variant": args.variant,
                    "T_out": int(pl.T_out), "streams": cfg.streams,
                    "head_tokens_per_s": cfg.streams * cfg.T / (ms_per_step * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "split_pass_kernel", "kernel_ms_avg": kern_avg_ms,
+                     "kernel": kernel, "kernel_ms_avg": kern_avg_ms,
                      "kernel_ms_min": min(kern_ms), "algorithmic_bytes": alg},
     }
-    if not args.no_cpu:
+    if not args.no_cpu and args.variant == "lag":
         ids = synth.stream_sample(cfg.streams, args.cpu_streams)
         res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H)
     return res
@@ -279,6 +286,8 @@ def main():
     ap.add_argument("--cpu-streams", type=int, default=32)
     ap.add_argument("--no-page-warmup", action="store_true",
                     help="skip the allocate/release cycle done before the timed buffers are created")
+    ap.add_argument("--variant", choices=["lag", "local", "l2"], default="lag",
+                    help="scoring: Eq. 7-11 (default), LocalKV Eq. 14-15, L2 norm Eq. 16")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--decode-batch", type=int, default=0)
