@@ -84,7 +84,6 @@ int strides_of(const lagkv_params* p, const Norm& n, int64_t T, int64_t* sb, int
 }
 
 bool shape_fused(const Norm& n, int64_t sb, int64_t sh, int64_t st) {
-  if (n.variant == LAGKV_SCORE_L2) return false;
   if (n.rowbytes != 64 && n.rowbytes != 128 && n.rowbytes != 256 && n.rowbytes != 512) return false;
   return ((sb | sh | st) & 15) == 0;
 }
@@ -246,7 +245,9 @@ size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T) {
   if (validate(p, &n) != LAGKV_OK || T < 1 || T > kMaxRows) return 0;
   int64_t sb, sh, st;
   if (strides_of(p, n, T, &sb, &sh, &st) != LAGKV_OK) return 0;
-  const bool fused = g_tune[LAGKV_TUNE_PATH] != 2 && shape_fused(n, sb, sh, st) && fused_fits(n);
+  // (the append of the L2 variant always takes the three-kernel path and needs its staging)
+  const bool fused = g_tune[LAGKV_TUNE_PATH] != 2 && shape_fused(n, sb, sh, st) && fused_fits(n) &&
+                     n.variant != LAGKV_SCORE_L2;
   if (fused) return 0;
   // one pass over T rows, and an append into a cache of capacity T
   lagkv_plan_t pl;
@@ -383,7 +384,7 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
   const int64_t q = tail >= 2 * (int64_t)n.L ? tail / n.L - 1 : 0;
   hipStream_t s = (hipStream_t)hip_stream;
   const int64_t force = g_tune[LAGKV_TUNE_PATH];
-  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
+  const bool fused_ok = n.variant != LAGKV_SCORE_L2 && shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, c->K, c->V, K_new, V_new);
   if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
   hipError_t e = hipSuccess;

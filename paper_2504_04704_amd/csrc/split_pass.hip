@@ -288,6 +288,42 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
   };
 
+  if (a.variant == 2) {
+    // Eq. 16: score = -||K_t||_2.  No reference and no softmax; V is read only where it is kept.
+    // All wavefronts share the K rows of the chunk.
+    const int R2 = nw * RPW, r2 = wave * RPW + rl;
+    const int n_iter2 = (L + R2 - 1) / R2;
+    for (int64_t p = p1 - 1; p >= p0; --p) {
+      const char* cb = kin + (S + p * L) * a.st + coff;
+      for (int it = 0; it < n_iter2; it += U) {
+        uint4 q[U];
+        int r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          r[u] = r2 + (it + u) * R2;
+          q[u] = ld16(cb + (int64_t)(r[u] < L ? r[u] : L - 1) * a.st);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float x[VEC];
+          unpack<ET>(q[u], x);
+          float ss = 0.f;
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
+          ss = group_sum<LPR>(ss);
+          if (cl == 0 && r[u] < L) vK[r[u]] = -sqrtf(ss);
+        }
+      }
+      __syncthreads();
+      if (wave == 0) wave_topk_scores(vK, L, k, list, lane);
+      if (sout)
+        for (int i = tid; i < L; i += nthreads) sout[p * L + i] = vK[i];
+      __syncthreads();
+      if (gather) compact(p);
+    }
+    return;
+  }
+
   if (local) {
     for (int64_t p = p1 - 1; p >= p0; --p) {
       const int64_t crow = S + p * L;

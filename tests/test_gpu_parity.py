@@ -160,12 +160,29 @@ def test_degenerate_channel_and_duplicate_tokens(path):
     assert sc[3] == sc[10]
 
 
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
 @pytest.mark.parametrize("variant", [lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
-@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 48)])
-def test_scoring_variants(variant, dtype, D):
-    say("variant", variant, dtype, D)
-    K, V = gen(1, 2, 16 + 5 * 64 + 3, D, dtype, seed=31 + variant)
-    run_and_check(K, V, 16, 64, 0.25, variant=variant)
+@pytest.mark.parametrize("dtype,D,L,r", [(torch.bfloat16, 128, 64, 0.25), (torch.float32, 48, 64, 0.25),
+                                         (torch.bfloat16, 128, 512, 0.125), (torch.float16, 64, 100, 0.33),
+                                         (torch.float32, 128, 24, 0.5)])
+def test_scoring_variants(variant, dtype, D, L, r, path):
+    say("variant", variant, dtype, D, L, "path", path)
+    if path == lagkv.PATH_FUSED and D == 48:
+        pytest.skip("192-byte rows are served by the three-kernel path only")
+    K, V = gen(2, 2, 16 + 5 * L + 3, D, dtype, seed=31 + variant)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    run_and_check(K, V, 16, L, r, variant=variant)
+
+
+@pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
+def test_l2_scores_need_no_values(path):
+    """Eq. 16 reads K only: lagkv_score accepts V = NULL for it."""
+    K, _ = gen(1, 2, 8 + 4 * 128, 128, torch.bfloat16, seed=77)
+    lagkv.tune(lagkv.TUNE_PATH, path)
+    sc = lagkv.score(K, None, 8, 128, 0.25, variant=lagkv.SCORE_L2)
+    torch.cuda.synchronize()
+    want = -torch.linalg.vector_norm(K[:, :, 8:8 + 3 * 128].double(), dim=-1)
+    assert torch.allclose(sc.double(), want, rtol=1e-5, atol=0)
 
 
 def test_ddof_zero():
