@@ -7,8 +7,12 @@ already resident in HBM.  Default workload: the 128K-context headline
 configuration (Llama-3-8B-shaped bf16 cache, 32 layers x 8 KV heads x D=128, B=4,
 T=131072, S=16, L=512, r=0.25; 64 GiB scanned per pass).
 
-Prints ONE JSON line (see README for the fields).  `--workload decode`
-times the decode-time variant (config 5) instead.
+Prints ONE JSON line: metric/value/unit (KV tokens per second, a token being one
+(batch, position) over all layers and heads), ms_per_step, config, `roofline` (achieved
+algorithmic GB/s of the kernel against the 8 TB/s HBM peak, measured with HIP events; HBM
+traffic from the recorded counters) and `cpu_baseline` (the fp64 oracle on a sample of the
+same streams).  `--workload decode` times the decode-time step (config 5) instead,
+`--variant` the LocalKV / L2-norm scoring ablations.
 """
 from __future__ import annotations
 

@@ -59,7 +59,7 @@ typedef enum {
 typedef struct {
   int32_t B, H, D;     /* batch (x layers), KV heads, head dimension (D >= 1; D >= 2 if std_ddof=1) */
   int32_t S, L;        /* sink size S >= 0 and lag size L >= 1 (bullets 2-4 of subsection LagKV)     */
-  double r;            /* retention ratio in (0, 1]; k = floor(r*L) must be >= 1 ("only rL tokens")  */
+  double r;            /* retention ratio in (0, 1]; k = floor(r*L) rows kept per chunk, must be >= 1   */
   int32_t dtype;       /* lagkv_dtype of K and V                                                     */
   int32_t variant;     /* lagkv_variant                                                              */
   int32_t std_ddof;    /* divisor of the channel-wise std is D - std_ddof; 1 (default reading) or 0  */
@@ -79,7 +79,7 @@ typedef struct {
 /*
  * Host-only arithmetic of the partition bullets and Eq. 12-13.  n_static < 0
  * means "fresh cache" (n_static = S).  When T - n_static < 2L the pass is a
- * no-op ("skip the compression"): n_scored = 0 and T_out = T; not an error.
+ * no-op (nothing is compressed below S + 2L): n_scored = 0 and T_out = T; not an error.
  */
 int lagkv_plan(const lagkv_params* p, int64_t T, int64_t n_static, lagkv_plan_t* out);
 
@@ -118,8 +118,8 @@ int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T,
                 float* scores, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Per-chunk, per-head top-k ("use the top-K strategy to select tokens in each
- * partition and each head").
+ * Per-chunk, per-head top-k (the selection step after Eq. 11: every head keeps its own
+ * k best rows of every chunk).
  *   scores  [B,H,n_scored*L] device fp32 as written by lagkv_score
  *   kept    [B,H,n_scored,k] device int32: absolute row positions (S + p*L + t)
  *           of the k highest scores of chunk p, ASCENDING.  Equal scores: the
@@ -143,8 +143,8 @@ int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t 
                    void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Decode-time cache under recursive compression ("recursively compressing KV
- * cache in both prefill and decode").  All buffers are caller-owned device
+ * Decode-time cache under recursive compression (Methodology: the same pass is applied
+ * again whenever the uncompressed tail has grown by one lag, in prefill and in decode).  All buffers are caller-owned device
  * memory, dense [B,H,capacity,D] (p->stride_* describe K_new/V_new only).
  * The four counters are host integers, identical for every stream, and are
  * updated by lagkv_append_and_compress before it returns (the device work is

@@ -8,15 +8,16 @@ tests, the smoke check and the benchmark's CPU-baseline leg may call it.
 
 What each function follows:
 
-  plan()                 bullets "keep the sink / skip below 2L / partition with
-                         L, remainder joins the sliding window" and Eq. 12-13
+  plan()                 the partition rules of subsection LagKV (sink kept, nothing
+                         done below S + 2L, chunks of L, the remainder belongs to
+                         the sliding window) and Eq. 12-13
   reference_min_max()    Eq. 7-8   (per-channel min/max over the sequence axis
                          of the NEXT chunk)
   normalise()            Eq. 9
   token_spread()         Eq. 10, "Std." part (std over a token's channels)
   chunk_softmax()        Eq. 10, "Softmax" part (over the chunk's L tokens)
   chunk_score()          Eq. 11    (score(K) + score(V))
-  top_k()                bullet "top-K per partition and per head", k = r*L
+  top_k()                selection step after Eq. 11: per chunk and per head, k = floor(r*L)
   compress()             the whole pass for one stream, compaction included
   IncrementalCache       the recursive / decode-time use of the same pass
   variants "local","l2"  Eq. 14-15 and Eq. 16 of the Scoring Methods ablation
@@ -49,7 +50,7 @@ VARIANTS = ("lag", "local", "l2")
 # partitioning and the closed-form output length (Eq. 12-13)
 # --------------------------------------------------------------------------
 def keep_count(L: int, r: float) -> int:
-    """Tokens kept per chunk, k = floor(r*L) ("only rL tokens will be kept")."""
+    """Tokens kept per chunk, k = floor(r*L) (the text around Eq. 12)."""
     k = int(math.floor(float(r) * int(L)))
     if not (1 <= k <= L):
         raise ValueError(f"k = floor(r*L) = {k} must lie in [1, L]")
@@ -67,7 +68,7 @@ def plan(T: int, S: int, L: int, r: float, n_static: Optional[int] = None) -> Di
         n_static = S
     k = keep_count(L, r)
     rest = T - n_static
-    if rest < 2 * L:                         # "skip the compression"
+    if rest < 2 * L:                         # below S + 2L nothing is compressed
         return dict(n_chunks=max(rest, 0) // L, n_scored=0, rem=max(rest, 0) % L, k=k, T_out=T)
     n = rest // L
     m = rest % L

@@ -56,7 +56,7 @@ int validate(const lagkv_params* p, Norm* n) {
 void plan_of(const Norm& n, int64_t T, int64_t n_static, lagkv_plan_t* out) {
   const int64_t rest = T - n_static;
   out->k = n.k;
-  if (rest < 2 * (int64_t)n.L) {  // "skip the compression"
+  if (rest < 2 * (int64_t)n.L) {  // below 2L rows after the static part nothing is compressed
     const int64_t r = rest > 0 ? rest : 0;
     out->n_chunks = r / n.L;
     out->rem = r % n.L;

@@ -319,8 +319,8 @@ class Cache:
 
 
     def prefill_chunked(self, K: torch.Tensor, V: torch.Tensor) -> int:
-        """Chunk-by-chunk compression during prefill (Ablation, "Chunk-by-Chunk Compression in
-        Prefill Stage"): the first S + 2L rows in one call, then L rows per call until all rows
+        """Chunk-by-chunk compression during prefill (Ablation, subsection on the prefill
+        stage): the first S + 2L rows in one call, then L rows per call until all rows
         are in; every call is lagkv_append_and_compress.  The model forward that would produce
         each slice between the calls is the caller's; here the rows are given.  Returns the
         number of calls made."""
