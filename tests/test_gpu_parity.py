@@ -78,6 +78,8 @@ SHAPES = [
     (3, 2, 1 + 9 * 3, 16, torch.float32, 1, 3, 0.67),                # tiny L
     (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.02),        # k = 1
     (1, 2, 3 + 5 * 64 + 9, 128, torch.bfloat16, 3, 64, 0.99),        # k = L - 1
+    (1, 1, 16 + 3 * 4096 + 5, 128, torch.bfloat16, 16, 4096, 0.25),  # long lag: keys and scores through LDS
+    (1, 1, 4 + 2 * 6000, 64, torch.bfloat16, 4, 6000, 0.001),        # near the largest lag the LDS budget serves
     (2, 2, 16 + 4 * 128 + 50, 128, torch.float16, 16, 128, 0.25),    # fp16, ring path
     (1, 2, 7 + 5 * 100 + 3, 64, torch.float16, 7, 100, 0.167),       # fp16, register path, r*L = 16.7
 ]
