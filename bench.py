@@ -289,7 +289,8 @@ def main():
     ap.add_argument("--workload", choices=["compress", "decode", "copy"], default="compress")
     ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
-    ap.add_argument("--cpu-streams", type=int, default=32)
+    ap.add_argument("--cpu-streams", type=int, default=96,
+                    help="streams the CPU oracle baseline is timed on (about 10-15 s of CPU work)")
     ap.add_argument("--no-page-warmup", action="store_true",
                     help="skip the allocate/release cycle done before the timed buffers are created")
     ap.add_argument("--variant", choices=["lag", "local", "l2"], default="lag",
