@@ -275,7 +275,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
 #pragma unroll
       for (int u = 0; u < UG; ++u) {
         const int s = s0 + u * R;
-        g[u] = ld16(src + (int64_t)list[s < k ? s : s0] * a.st);
+        g[u] = ld16_last(src + (int64_t)list[s < k ? s : s0] * a.st);
       }
 #pragma unroll
       for (int u = 0; u < UG; ++u) {
