@@ -78,12 +78,4 @@ __device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
 __device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 
-// one landed LDS word (assembly: not ordered behind asynchronous loads in flight)
-__device__ __forceinline__ uint32_t lds_load_u32(uint32_t addr) {
-  uint32_t v;
-  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
-  return v;
-}
-__device__ __forceinline__ void vmem_drain() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 }  // namespace lagkv
