@@ -169,6 +169,7 @@ def bench_compress(args):
         "config": {"workload": cfg.name, "layers": cfg.layers, "B": cfg.B, "H_kv": cfg.H, "D": cfg.D,
                    "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype, "variant": args.variant,
                    "T_out": int(pl.T_out), "streams": cfg.streams,
+                   "placement_rehearsal": not args.no_page_warmup,
                    "head_tokens_per_s": cfg.streams * cfg.T / (ms_per_step * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
