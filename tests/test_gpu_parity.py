@@ -418,3 +418,42 @@ def test_config5_decode_rounds_reduced_batch():
     for s in synth.stream_sample(cfg.streams, 6):
         b, h = divmod(s, cfg.H)
         PU.check_stream(Kh[b, h], Vh[b, h], cfg.S, cfg.L, cfg.r, gpos[b, h], gK[b, h], gV[b, h])
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("L", [128, 512])     # 512: the launch that opts in to more than 64 KiB of LDS
+def test_compress_can_be_captured_in_a_graph_and_replayed(L):
+    """The pass enqueues kernels only (no allocation, no memset, no synchronisation), so a
+    caller may capture it in a HIP graph.  Replays, with eager work between them, must all
+    reproduce the eager result."""
+    S, r = 16, 0.25
+    K, V = gen(2, 4, S + 9 * L + 17, 128, torch.bfloat16, seed=404)
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
+    eager = lagkv.compress(K, V, S, L, r)
+    torch.cuda.synchronize()
+    Ko, Vo = torch.zeros_like(eager.K), torch.zeros_like(eager.V)
+    idx = torch.zeros_like(eager.idx)
+    ws = torch.empty(max(lagkv.workspace_bytes(lagkv.params_for(K, S, L, r), K.shape[2]), 16), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up on the capture stream
+        lagkv.compress(K, V, S, L, r, out=(Ko, Vo), idx_out=idx, ws=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        lagkv.compress(K, V, S, L, r, out=(Ko, Vo), idx_out=idx, ws=ws)
+    for rep in range(3):
+        Ko.zero_(); Vo.zero_(); idx.zero_()             # eager work between the replays
+        _ = (K.float().sum() + rep).item()
+        g.replay()
+        torch.cuda.synchronize()
+        say("graph replay", rep)
+        assert torch.equal(Ko, eager.K) and torch.equal(Vo, eager.V) and torch.equal(idx, eager.idx)
+    # new input bytes in the same buffers: the replay follows them
+    K2, V2 = gen(2, 4, S + 9 * L + 17, 128, torch.bfloat16, seed=405)
+    K.copy_(K2); V.copy_(V2)
+    g.replay()
+    torch.cuda.synchronize()
+    fresh = lagkv.compress(K, V, S, L, r)
+    torch.cuda.synchronize()
+    assert torch.equal(Ko, fresh.K) and torch.equal(idx, fresh.idx)
