@@ -23,6 +23,9 @@
 #ifndef LAGKV_SPLIT_DMA
 #define LAGKV_SPLIT_DMA 1    // 1: asynchronous global->LDS row loads when the rows of a chunk divide evenly
 #endif
+#ifndef LAGKV_LOCAL_REV
+#define LAGKV_LOCAL_REV 1     // LocalKV: second pass over a chunk in reverse row order
+#endif
 #ifndef LAGKV_SPLIT_WPE
 #define LAGKV_SPLIT_WPE 4    // wavefronts per SIMD the register budget is set for
 #endif
@@ -175,11 +178,14 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const uint32_t ring_lds = lds_offset(lds + lay.off_ring) + (uint32_t)wave * (kRing * 1024u);
   const uint32_t ring_lane = ring_lds + (uint32_t)lane * 16u;
   const uint32_t var_lds = lds_offset(myvar) + (uint32_t)row0 * 4u;
-  auto scan_dma = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+  // rev: walk the steps of the chunk from the last to the first (used for a second pass over a chunk,
+  // whose most recently read rows are the ones still in the L2)
+  auto scan_dma = [&](int64_t row, bool rev, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
     constexpr bool STATS = decltype(stats_tag)::value, SCORE = decltype(score_tag)::value;
     const char* ubase = tin + row * a.st;  // wave-uniform
+    auto phys = [&](int step) __attribute__((always_inline)) { return rev ? n_iter - 1 - step : step; };
     auto dma = [&](int step) __attribute__((always_inline)) {
-      __builtin_amdgcn_global_load_lds((gptr_t)(ubase + (int64_t)step * R * a.st + lane_off),
+      __builtin_amdgcn_global_load_lds((gptr_t)(ubase + (int64_t)phys(step) * R * a.st + lane_off),
                                        (lptr_t)(lds + lay.off_ring + (wave * kRing + step % kRing) * 1024),
                                        16, 0, 0);
     };
@@ -198,8 +204,8 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
         const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
         if (cl == 0) {
-          lds_store_f32(var_lds + (uint32_t)(s * R) * 4u, v0);
-          if (s + 1 < n_iter) lds_store_f32(var_lds + (uint32_t)((s + 1) * R) * 4u, v1);
+          lds_store_f32(var_lds + (uint32_t)(phys(s) * R) * 4u, v0);
+          if (s + 1 < n_iter) lds_store_f32(var_lds + (uint32_t)(phys(s + 1) * R) * 4u, v1);
         }
       }
     };
@@ -226,8 +232,8 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     }
     lds_drain();
   };
-  auto scan = [&](int64_t row, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
-    if constexpr (use_dma) scan_dma(row, stats_tag, score_tag);
+  auto scan = [&](int64_t row, bool rev, auto stats_tag, auto score_tag) __attribute__((always_inline)) {
+    if constexpr (use_dma) scan_dma(row, rev, stats_tag, score_tag);
     else scan_regs(row, stats_tag, score_tag);
   };
   // combine acc over the row groups of a wavefront and the wavefronts of the tensor
@@ -328,10 +334,10 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     for (int64_t p = p1 - 1; p >= p0; --p) {
       const int64_t crow = S + p * L;
       acc.reset();
-      scan(crow, T_{}, F_{});
+      scan(crow, false, T_{}, F_{});
       fold();
       ref.from(acc);
-      scan(crow, F_{}, T_{});
+      scan(crow, LAGKV_LOCAL_REV != 0, F_{}, T_{});
       __syncthreads();
       if (wave == 0)
         wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
@@ -343,13 +349,13 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
 
   // statistics of the chunk after the segment: the first reference
   acc.reset();
-  scan(S + p1 * L, T_{}, F_{});
+  scan(S + p1 * L, false, T_{}, F_{});
   fold();
   ref.from(acc);
   __syncthreads();  // statbuf is rewritten by the next fold
   for (int64_t p = p1 - 1; p >= p0; --p) {
     acc.reset();
-    scan(S + p * L, T_{}, T_{});
+    scan(S + p * L, false, T_{}, T_{});
     fold();  // barrier inside: the variances are visible
     ref.from(acc);  // chunk p is the reference of chunk p-1 (done before the selection so
                     // that the running statistics are dead across it: fewer live registers)
