@@ -457,3 +457,54 @@ def test_compress_can_be_captured_in_a_graph_and_replayed(L):
     fresh = lagkv.compress(K, V, S, L, r)
     torch.cuda.synchronize()
     assert torch.equal(Ko, fresh.K) and torch.equal(idx, fresh.idx)
+
+
+def test_config5_decode_full_batch_sampled_streams():
+    """Config 5 at its real size (B = 32: 8192 streams, the launch bench.py --workload decode
+    times), 16 of the 64 rounds: the compressed starting cache is built layer by layer (the
+    uncompressed one would be 128 GiB), the history of a sample of streams is kept on the host,
+    and their final caches are compared with the one-shot oracle on that history."""
+    cfg = synth.CONFIGS["cfg5_decode_b32"]
+    rounds = 16
+    say("config 5 full batch", cfg.streams, "streams")
+    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
+    pl = lagkv.plan(lagkv.make_params(cfg.layers * cfg.B, cfg.H, cfg.D, cfg.S, cfg.L, cfg.r), cfg.T)
+    assert pl.T_out == 8384
+    cap = pl.T_out + rounds * pl.k + cfg.L
+    cache = lagkv.Cache(cfg.layers * cfg.B, cfg.H, cfg.D, cap, cfg.S, cfg.L, cfg.r, track_positions=True)
+    sample = synth.stream_sample(cfg.streams, 12)
+    hist = {s: ([], []) for s in sample}
+    Kl = torch.empty((cfg.B, cfg.H, cfg.T, cfg.D), dtype=torch.bfloat16, device=DEV)
+    Vl = torch.empty_like(Kl)
+    for l in range(cfg.layers):
+        synth.fill_layer(cfg, synth.MASTER_SEED, l, Kl, Vl)
+        comp = lagkv.compress(Kl, Vl, cfg.S, cfg.L, cfg.r)
+        sl = slice(l * cfg.B, (l + 1) * cfg.B)
+        cache.K[sl, :, :pl.T_out].copy_(comp.K)
+        cache.V[sl, :, :pl.T_out].copy_(comp.V)
+        cache.pos[sl, :, :pl.T_out].copy_(comp.idx)
+        for s in sample:
+            bb, h = divmod(s, cfg.H)
+            if l * cfg.B <= bb < (l + 1) * cfg.B:
+                hist[s][0].append(Kl[bb - l * cfg.B, h].cpu())
+                hist[s][1].append(Vl[bb - l * cfg.B, h].cpu())
+    del Kl, Vl, comp
+    n_static = cfg.S + pl.k * pl.n_scored
+    cache.c.n_static, cache.c.n_tail, cache.c.n_seen = n_static, pl.T_out - n_static, cfg.T
+    for i in range(rounds):
+        Kn, Vn = synth.make_new_tokens(cfg, cfg.L, i, device=DEV)
+        cache.append_and_compress(Kn, Vn)
+        for s in sample:
+            bb, h = divmod(s, cfg.H)
+            hist[s][0].append(Kn[bb, h].cpu())
+            hist[s][1].append(Vn[bb, h].cpu())
+        assert cache.n_tail == 240 and cache.length == 8384 + 32 * (i + 1)
+    torch.cuda.synchronize()
+    gK, gV, gpos = cache.view()
+    T_hist = cfg.T + rounds * cfg.L
+    PU.check_index_invariants(gpos, T_hist, cfg.S, cfg.L, 32, 254 + rounds)
+    for s in sample:
+        bb, h = divmod(s, cfg.H)
+        Kh, Vh = torch.cat(hist[s][0], dim=0), torch.cat(hist[s][1], dim=0)
+        assert Kh.shape[0] == T_hist
+        PU.check_stream(Kh, Vh, cfg.S, cfg.L, cfg.r, gpos[bb, h], gK[bb, h], gV[bb, h])
