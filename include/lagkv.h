@@ -100,8 +100,9 @@ int lagkv_keep_for_compression(int64_t T, int32_t S, int32_t L, double C, int64_
  * Device workspace, in bytes, that lagkv_score / lagkv_compress /
  * lagkv_append_and_compress need for these parameters and T rows (for append:
  * T = cache capacity).  0 when the fused kernels serve the shape; the
- * three-kernel path used for unaligned or unusual shapes stages scores and
- * kept positions there.  Returns 0 on invalid parameters as well.
+ * three-kernel path used for unaligned or unusual shapes (and for appends of
+ * the LAGKV_SCORE_L2 variant) stages scores and kept positions there.
+ * Returns 0 on invalid parameters as well.
  */
 size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T);
 
@@ -110,7 +111,8 @@ size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T);
  *   K, V    [B,H,T,D] device, dtype p->dtype (V may be NULL for LAGKV_SCORE_L2)
  *   scores  [B,H,n_scored*L] device fp32, dense; entry j of a stream belongs to
  *           row S + j.  Within a chunk the scores are softmax(std(Kbar)) +
- *           softmax(std(Vbar)) and sum to 2.
+ *           softmax(std(Vbar)) and sum to 2 (LAG, LOCAL); for LAGKV_SCORE_L2
+ *           they are -||K_t||_2.
  * A reference channel with max == min contributes 0 to every token.
  * n_scored == 0: returns LAGKV_OK and writes nothing.
  */
