@@ -96,15 +96,12 @@ def bench_compress(args):
     cfg = synth.CONFIGS[args.config]
     dev = "cuda:0"
     lagkv.load()
-    if args.waves:
-        lagkv.tune(lagkv.TUNE_WAVES, args.waves)
-    if args.segments:
-        lagkv.tune(lagkv.TUNE_SEGMENTS, args.segments)
+    launch = lagkv.launch_hint(args.path, args.waves, args.segments, args.order, args.select)
     variant = {"lag": lagkv.SCORE_LAG, "local": lagkv.SCORE_LOCAL, "l2": lagkv.SCORE_L2}[args.variant]
 
     def build_working_set():
         K, V = synth.make_kv(cfg, device=dev)
-        p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r, variant=variant)
+        p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r, variant=variant, launch=launch)
         pl = lagkv.plan(p, cfg.T)
         Bf, H, T, D = K.shape
         Ko = torch.empty((Bf, H, pl.T_out, D), dtype=K.dtype, device=dev)
@@ -114,11 +111,11 @@ def bench_compress(args):
 
     def quick_ms(ws_set, n=3):
         K, V, Ko, Vo, idx = ws_set[:5]
-        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx)
+        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, launch=launch)
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s.record()
         for _ in range(n):
-            lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx)
+            lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, launch=launch)
         e.record()
         torch.cuda.synchronize()
         return s.elapsed_time(e) / n
@@ -154,7 +151,7 @@ def bench_compress(args):
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
 
     def step():
-        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, ws=ws)
+        lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, ws=ws, launch=launch)
 
     for _ in range(args.warmup):
         step()
@@ -231,7 +228,7 @@ def bench_decode(args):
         cache.V[sl, :, :pl.T_out].copy_(comp.V)
         cache.pos[sl, :, :pl.T_out].copy_(comp.idx)
     del Kl, Vl, comp, one
-    cache.c.n_static, cache.c.n_tail, cache.c.n_seen = cfg.S + pl.k * pl.n_scored, pl.T_out - (cfg.S + pl.k * pl.n_scored), cfg.T
+    cache.mark_compressed(cfg.T)
     torch.cuda.synchronize()
     new = [synth.make_new_tokens(cfg, cfg.L, i % 4, device=dev) for i in range(4)]
     lat = []
@@ -320,8 +317,11 @@ def main():
                     help="time the first allocation of the working set (no placement trials)")
     ap.add_argument("--variant", choices=["lag", "local", "l2"], default="lag",
                     help="scoring: Eq. 7-11 (default), LocalKV Eq. 14-15, L2 norm Eq. 16")
+    ap.add_argument("--path", type=int, default=0, help="launch hint: 0 auto, 1 fused, 2 three-kernel, 3 register-resident")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--order", type=int, default=0, help="launch hint: workgroup-to-stream order")
+    ap.add_argument("--select", type=int, default=0, help="launch hint: selection mode")
     ap.add_argument("--decode-batch", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -21,7 +21,8 @@
  *     (hipStream_t passed as void*, NULL = default stream) and return without
  *     synchronising.  Output sizes are pure functions of (T, S, L, k), see
  *     lagkv_plan.  Nothing is enqueued when validation fails.
- *   - The library allocates no device memory and keeps no per-call state.
+ *   - The library allocates no device memory and keeps no state between calls: every
+ *     call is a function of its arguments (launch overrides travel in lagkv_params).
  *   - Return value: a lagkv_status.  Inputs must be finite; NaN/Inf give
  *     unspecified scores (never out-of-bounds accesses).
  *   - Arithmetic: inputs as stored (fp32, bf16 or fp16), all scoring math in fp32,
@@ -63,7 +64,7 @@ typedef struct {
   int32_t dtype;       /* lagkv_dtype of K and V                                                     */
   int32_t variant;     /* lagkv_variant                                                              */
   int32_t std_ddof;    /* divisor of the channel-wise std is D - std_ddof; 1 (default reading) or 0  */
-  int32_t reserved;    /* must be 0                                                                  */
+  int32_t launch;      /* 0 = automatic launch choice, else a value returned by lagkv_launch_hint()   */
   int64_t stride_b, stride_h, stride_t; /* INPUT strides in elements; 0 = dense [B,H,T,D]           */
 } lagkv_params;
 
@@ -97,12 +98,14 @@ int lagkv_keep_for_compression(int64_t T, int32_t S, int32_t L, double C, int64_
                                double* r_out);
 
 /*
- * Device workspace, in bytes, that lagkv_score / lagkv_compress /
- * lagkv_append_and_compress need for these parameters and T rows (for append:
- * T = cache capacity).  0 when the fused kernels serve the shape; the
- * three-kernel path used for unaligned or unusual shapes (and for appends of
- * the LAGKV_SCORE_L2 variant) stages scores and kept positions there.
- * Returns 0 on invalid parameters as well.
+ * Device workspace, in bytes, that lagkv_compress / lagkv_append_and_compress need for
+ * these parameters (p->launch included) and T rows (for append: T = cache capacity, the
+ * bound that holds for any single append).  0 when the fused kernels serve the shape: rows
+ * of 64, 128, 256 or 512 bytes, strides that are multiples of 16 bytes, a lag that fits
+ * the LDS budget.  The three-kernel path used for every other shape stages scores and kept
+ * positions there.  The answer assumes 16-byte aligned K / V / output / cache pointers (any
+ * hipMalloc'ed buffer is); a caller whose pointers are only element-aligned must ask, and
+ * call, with a launch hint of LAGKV_PATH_STAGED.  Returns 0 on invalid parameters as well.
  */
 size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T);
 
@@ -115,6 +118,8 @@ size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T);
  *           they are -||K_t||_2.
  * A reference channel with max == min contributes 0 to every token.
  * n_scored == 0: returns LAGKV_OK and writes nothing.
+ * ws / ws_bytes: unused (every path writes the scores straight to `scores`); kept so
+ * that the three device calls share one argument pattern.  May be NULL / 0.
  */
 int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T,
                 float* scores, void* ws, size_t ws_bytes, void* hip_stream);
@@ -163,31 +168,71 @@ typedef struct {
 } lagkv_cache;
 
 /*
+ * Host only: set the counters of `cache` to the state of a cache that holds the output of
+ * lagkv_compress on T rows (Eq. 12: n_static = S + k*n_scored, n_tail = L + rem,
+ * n_seen = T; when T - S < 2L nothing was compressed: n_static = min(T, S),
+ * n_tail = T - n_static).  Buffers and capacity are left as they are.
+ * LAGKV_ECAPACITY if capacity < T_out, LAGKV_EINVAL on null pointers.
+ */
+int lagkv_cache_after_compress(const lagkv_params* p, int64_t T, lagkv_cache* cache);
+
+/*
+ * Host only: rows to hand to the next lagkv_append_and_compress call when a prompt is
+ * compressed chunk by chunk during prefill (Ablation, prefill-stage compression): the
+ * first call of an empty cache takes S + 2L rows (the shortest prefix that compresses
+ * anything), every later call one lag L, both capped by rows_left.  Returns 0 when
+ * rows_left <= 0 or on invalid arguments.
+ */
+int64_t lagkv_prefill_rows(const lagkv_params* p, const lagkv_cache* cache, int64_t rows_left);
+
+/*
  * Append n_new rows per stream (K_new, V_new: [B,H,n_new,D] with p->stride_*,
  * 0 = dense), then, while the tail holds at least 2L rows, score its oldest L
  * rows against the next L, keep k of them right after the static part and
  * slide the remaining tail down.  Equivalent to lagkv_compress on the whole
  * history.  n_new = 0 is allowed.  Needs capacity >= n_static + n_tail + n_new.
- * The cache of lagkv_compress's output is: n_static = S + k*n_scored,
- * n_tail = L + rem, n_seen = T.
+ * All three scoring variants run in one fused kernel per call when the shape allows
+ * (see lagkv_workspace_bytes); ws is used by the three-kernel path only.
  */
 int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const void* K_new,
                               const void* V_new, int64_t n_new, void* ws, size_t ws_bytes,
                               void* hip_stream);
 
 /*
- * Launch tuning for benchmarks and tests (process-global, not thread-safe
- * against concurrent calls).  key: LAGKV_TUNE_*; value 0 restores the
- * automatic choice.  Returns LAGKV_EINVAL for an unknown key or a value the
- * kernels do not support.
+ * Launch override for benchmarks, tests and sweeps.  A pure function: it packs its
+ * arguments into the value lagkv_params.launch carries for ONE call; the library keeps
+ * nothing.  0 in any argument means "choose automatically" (and launch = 0 is the same as
+ * lagkv_launch_hint(0, 0, 0)).
+ *   path      LAGKV_PATH_AUTO; LAGKV_PATH_FUSED (error LAGKV_ESHAPE when the fused kernels
+ *             do not cover the shape); LAGKV_PATH_STAGED (three-kernel path); or
+ *             LAGKV_PATH_RESIDENT (the one-shot kernel that keeps a batch of rows in
+ *             registers and reads every row once: 256-byte rows, L of 128, 256 or 512,
+ *             not Eq. 16; LAGKV_ESHAPE otherwise; append calls treat it as FUSED)
+ *   waves     wavefronts per workgroup of the fused kernels: 1 (append only), 2, 4 or 8
+ *   segments  pieces each stream is cut into by the one-shot kernel, 1 .. 2^20
+ * Returns -1 for a value the kernels do not support.  lagkv_workspace_bytes must be
+ * asked with the same launch value as the call it sizes the workspace for.
  */
-enum {
-  LAGKV_TUNE_PATH = 0,       /* 0 auto, 1 force the fused kernels (error if unsupported), 2 force the three-kernel path */
-  LAGKV_TUNE_WAVES = 1,      /* wavefronts per workgroup of the fused kernels: 1 (append only), 2, 4, 8 */
-  LAGKV_TUNE_SEGMENTS = 2,   /* segments each stream is cut into by the fused kernel (>= 1)         */
-  LAGKV_TUNE_COUNT = 3
-};
-int lagkv_tune(int key, int64_t value);
+enum { LAGKV_PATH_AUTO = 0, LAGKV_PATH_FUSED = 1, LAGKV_PATH_STAGED = 2, LAGKV_PATH_RESIDENT = 3 };
+int32_t lagkv_launch_hint(int path, int waves, int segments);
+
+/*
+ * lagkv_launch_hint with two further overrides (0 = automatic), for sweeps:
+ *   order   which stream the i-th workgroup takes: LAGKV_ORDER_LINEAR (stream i),
+ *           LAGKV_ORDER_EVEN_ODD (even streams first: the workgroups resident at one
+ *           time span the whole tensor), LAGKV_ORDER_XCD (i mod 8 picks one eighth of
+ *           the streams, so each of the eight L2 slices sees a contiguous eighth) or
+ *           LAGKV_ORDER_BITREV (bit-reversed i).  Orders whose precondition fails
+ *           (stream count not a multiple of 8 / not a power of two) fall back to LINEAR.
+ *   select  how a chunk's top-k is taken: LAGKV_SELECT_WAVE (one wavefront, a different
+ *           one for each chunk; bisection over the key bits with ballots) or
+ *           LAGKV_SELECT_GROUP (all wavefronts; four 8-bit digit histograms in LDS; needs
+ *           L <= threads of the workgroup, else WAVE).  The kept set is the same.
+ * Returns -1 for an unknown value.
+ */
+enum { LAGKV_ORDER_LINEAR = 0, LAGKV_ORDER_EVEN_ODD = 1, LAGKV_ORDER_XCD = 2, LAGKV_ORDER_BITREV = 3 };
+enum { LAGKV_SELECT_AUTO = 0, LAGKV_SELECT_WAVE = 1, LAGKV_SELECT_GROUP = 2 };
+int32_t lagkv_launch_hint_ex(int path, int waves, int segments, int order, int select);
 
 /* Static, human readable text for a lagkv_status. */
 const char* lagkv_strerror(int status);

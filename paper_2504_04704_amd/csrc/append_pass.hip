@@ -10,6 +10,7 @@
 #include "lagkv_internal.hpp"
 #include "row_ops.hpp"
 #include "wave_ops.hpp"
+#include "wg_select.hpp"
 #include "lds_dma.hpp"
 
 namespace lagkv {
@@ -291,16 +292,33 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
   for (int64_t j = 0; j < a.rounds; ++j) {
     const int64_t cur = base + j * L;      // rows of the chunk (not yet moved)
     const int64_t dst = base + j * k;      // where its kept rows go
-    acc.reset();
-    const int64_t refc = (a.variant == 1) ? cur : cur + L;  // Eq. 14-15 vs Eq. 7-8
-    scan_chunk<ET, LPR, true, false>(kc + refc * rowbytes, vc + refc * rowbytes, rowbytes, L, g, acc,
-                                     ref, inv_D, inv_dof, sK, sV);
-    fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
-    ref.from(acc);
-    scan_chunk<ET, LPR, false, true>(kc + cur * rowbytes, vc + cur * rowbytes, rowbytes, L, g, acc,
-                                     ref, inv_D, inv_dof, sK, sV);
-    __syncthreads();
-    if (g.wave == 0) wave_score_select_any(sK, sV, L, k, true, nullptr, list, nullptr, g.lane);
+    if (a.variant == 2) {
+      // Eq. 16: score = -||K_t||_2 from the chunk's keys alone; V is read only where it is kept
+      const int n_iter = (L + g.rps - 1) / g.rps;
+      for (int it = 0; it < n_iter; ++it) {
+        const int r = g.row0 + it * g.rps;
+        float x[VEC];
+        unpack<ET>(ld16(kc + (cur + (r < L ? r : L - 1)) * rowbytes + coff), x);
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ss = fmaf(x[i], x[i], ss);
+        ss = group_sum<LPR>(ss);
+        if (g.cl == 0 && r < L) sK[r] = -sqrtf(ss);
+      }
+      __syncthreads();
+      if (g.wave == 0) wave_topk_scores(sK, L, k, list, g.lane);
+    } else {
+      acc.reset();
+      const int64_t refc = (a.variant == 1) ? cur : cur + L;  // Eq. 14-15 vs Eq. 7-8
+      scan_chunk<ET, LPR, true, false>(kc + refc * rowbytes, vc + refc * rowbytes, rowbytes, L, g, acc,
+                                       ref, inv_D, inv_dof, sK, sV);
+      fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
+      ref.from(acc);
+      scan_chunk<ET, LPR, false, true>(kc + cur * rowbytes, vc + cur * rowbytes, rowbytes, L, g, acc,
+                                       ref, inv_D, inv_dof, sK, sV);
+      __syncthreads();
+      if (g.wave == 0) wave_score_select_any(sK, sV, L, k, true, nullptr, list, nullptr, g.lane);
+    }
     __syncthreads();
     // staged in-place gather of the kept rows
     constexpr int UB = 4;
@@ -339,7 +357,8 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
 
 // ---------------------------------------------------------------------------------
 // Single-round decode step: the common call, in which the appended rows complete
-// exactly one more chunk (2L <= tail + new < 3L, sink already full, Eq. 7-11 scoring).
+// exactly one more chunk (2L <= tail + new < 3L, sink already full; Eq. 7-11 scoring, or
+// Eq. 16 with the reference steps reduced to the row moves).
 // The new rows are never stored at the end of the tail first: the tail is addressed
 // "virtually" (row v lives in the cache when v < n_tail, else in K_new/V_new), every
 // row is read from memory once and written once at its final place:
@@ -351,7 +370,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
 // streams does not fit any cache, and the hints are worth 2.8 % (0.570 -> 0.554 ms per call).
 // ---------------------------------------------------------------------------------
 struct StepLds {
-  int off_vK, off_vV, off_list, off_pos, off_stat, off_stash, total;  // bytes
+  int off_vK, off_vV, off_list, off_sel, off_pos, off_stat, off_stash, total;  // bytes
 };
 __host__ __device__ inline StepLds step_lds(int D, int L, int k, int nw, int rowbytes) {
   StepLds l;
@@ -359,7 +378,8 @@ __host__ __device__ inline StepLds step_lds(int D, int L, int k, int nw, int row
   l.off_vK = 0;
   l.off_vV = lp * 4;
   l.off_list = 2 * lp * 4;
-  l.off_pos = l.off_list + kp * 4;               // positions of the (< 3L) tail rows
+  l.off_sel = l.off_list + kp * 4;               // scratch of the workgroup-wide selection
+  l.off_pos = l.off_sel + group_sel_bytes();     // positions of the (< 3L) tail rows
   l.off_stat = l.off_pos + 3 * lp * 4;           // [wave][mn|mx][D]
   l.off_stash = (l.off_stat + nw * 2 * D * 4 + 15) & ~15;  // [K|V][L][rowbytes]
   l.total = l.off_stash + 2 * L * rowbytes;
@@ -380,8 +400,11 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
   float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
   uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  uint32_t* selbuf = reinterpret_cast<uint32_t*>(lds + lay.off_sel);
   int32_t* ptail = reinterpret_cast<int32_t*>(lds + lay.off_pos);
   float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+  const bool l2 = a.variant == 2;        // Eq. 16: keys only, no reference statistics
+  const bool group_sel = a.sel == kSelGroup && L <= nthreads;
 
   const int tensor = wave >= G ? 1 : 0;  // 0: K rows, 1: V rows
   const int gslot = wave - tensor * G;
@@ -421,12 +444,14 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float x[VEC];
-      unpack<ET>(q[u], x);
+      if (!l2) {
+        float x[VEC];
+        unpack<ET>(q[u], x);
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) {
-        acc.mn[j] = fminf(acc.mn[j], x[j]);
-        acc.mx[j] = fmaxf(acc.mx[j], x[j]);
+        for (int j = 0; j < VEC; ++j) {
+          acc.mn[j] = fminf(acc.mn[j], x[j]);
+          acc.mx[j] = fmaxf(acc.mx[j], x[j]);
+        }
       }
       if (r[u] < L) *reinterpret_cast<uint4*>(mystash + (size_t)r[u] * rowbytes) = q[u];
     }
@@ -459,25 +484,43 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   TRef<VEC> ref;
   ref.from(acc);
 
-  // 2. the chunk (tail rows [0,L)): channel variance of every token (Eq. 9-10)
-  for (int it = 0; it < n_iter; it += U) {
-    uint4 q[U];
-    int r[U];
+  // 2. the chunk (tail rows [0,L)): channel variance of every token (Eq. 9-10), or, for
+  // Eq. 16, minus the key norm (the V wavefronts then read nothing here)
+  if (!l2 || tensor == 0) {
+    for (int it = 0; it < n_iter; it += U) {
+      uint4 q[U];
+      int r[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      r[u] = row0 + (it + u) * R;
-      q[u] = ld16(src(r[u] < L ? r[u] : L - 1));
-    }
+      for (int u = 0; u < U; ++u) {
+        r[u] = row0 + (it + u) * R;
+        q[u] = ld16(src(r[u] < L ? r[u] : L - 1));
+      }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float x[VEC];
-      unpack<ET>(q[u], x);
-      const float v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-      if (cl == 0 && r[u] < L) myvar[r[u]] = v;
+      for (int u = 0; u < U; ++u) {
+        float x[VEC];
+        unpack<ET>(q[u], x);
+        float v;
+        if (l2) {
+          float ss = 0.f;
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
+          v = -sqrtf(group_sum<LPR>(ss));
+        } else {
+          v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        }
+        if (cl == 0 && r[u] < L) myvar[r[u]] = v;
+      }
     }
   }
+  if (group_sel && l2) group_sel_clear(selbuf, tid, nthreads);
   __syncthreads();
-  if (wave == 0) wave_score_select_lean(vK, vV, L, k, true, nullptr, list, nullptr, lane);
+  if (group_sel) {
+    if (l2) group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
+    else group_score_select(vK, vV, L, k, true, nullptr, selbuf, list, nullptr, tid, nthreads);
+  } else if (wave == 0) {
+    if (l2) wave_topk_scores(vK, L, k, list, lane);
+    else wave_score_select_lean(vK, vV, L, k, true, nullptr, list, nullptr, lane);
+  }
   __syncthreads();
 
   // 3. kept rows -> [0,k).  A batch is loaded, the workgroup synchronises, the batch is
@@ -559,7 +602,7 @@ constexpr size_t kStepMaxLds = 80 * 1024;
 
 bool decode_step_supported(const AppendArgs& a) {
   const int lpr = lanes_per_row(a.D, a.esize);
-  if (lpr == 0 || a.variant != 0 || a.rounds != 1 || a.n_seen < a.S) return false;
+  if (lpr == 0 || a.variant == 1 || a.rounds != 1 || a.n_seen < a.S) return false;
   return (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total <= kStepMaxLds;
 }
 

@@ -11,7 +11,25 @@ using namespace lagkv;
 
 namespace {
 
-int64_t g_tune[LAGKV_TUNE_COUNT] = {0, 0, 0};
+// Launch override carried by lagkv_params.launch (see lagkv_launch_hint):
+//   bits 0-1 path, bits 2-5 wavefronts, bits 6-26 segments, bits 27-28 stream order,
+//   bits 29-30 selection mode; 0 everywhere = automatic.
+struct Hint {
+  int path, waves, nseg, order, sel;
+};
+constexpr int kHintWavesShift = 2, kHintSegShift = 6, kHintOrderShift = 27, kHintSelShift = 29;
+constexpr int kMaxSegments = 1 << 20;
+
+bool parse_hint(int32_t v, Hint* h) {
+  if (v < 0) return false;
+  h->path = v & 3;
+  h->waves = (v >> kHintWavesShift) & 15;
+  h->nseg = (v >> kHintSegShift) & ((1 << 21) - 1);
+  h->order = (v >> kHintOrderShift) & 3;
+  h->sel = (v >> kHintSelShift) & 3;
+  if (h->waves != 0 && h->waves != 1 && h->waves != 2 && h->waves != 4 && h->waves != 8) return false;
+  return h->nseg <= kMaxSegments && h->sel <= LAGKV_SELECT_GROUP;
+}
 
 constexpr int64_t kMaxRows = 0x7fffffffLL;  // positions are int32
 constexpr size_t kAlign = 256;
@@ -22,13 +40,14 @@ struct Norm {  // validated, normalised parameters
   int B, H, D, S, L, k, esize, f16, ddof, variant;
   int64_t streams;
   int64_t rowbytes;
+  Hint hint;
 };
 
 int validate(const lagkv_params* p, Norm* n) {
   if (!p) return LAGKV_EINVAL;
   if (p->dtype != LAGKV_F32 && p->dtype != LAGKV_BF16 && p->dtype != LAGKV_F16) return LAGKV_EDTYPE;
   if (p->variant < LAGKV_SCORE_LAG || p->variant > LAGKV_SCORE_L2) return LAGKV_EDTYPE;
-  if (p->reserved != 0) return LAGKV_EINVAL;
+  if (!parse_hint(p->launch, &n->hint)) return LAGKV_EINVAL;
   if (p->std_ddof != 0 && p->std_ddof != 1) return LAGKV_EINVAL;
   if (p->B < 1 || p->H < 1 || p->D < 1) return LAGKV_ESHAPE;
   if (p->std_ddof == 1 && p->D < 2 && p->variant != LAGKV_SCORE_L2) return LAGKV_ESHAPE;
@@ -89,7 +108,7 @@ bool shape_fused(const Norm& n, int64_t sb, int64_t sh, int64_t st) {
 }
 
 int pick_waves(const Norm& n) {
-  int nw = g_tune[LAGKV_TUNE_WAVES] ? (int)g_tune[LAGKV_TUNE_WAVES] : 4;
+  int nw = n.hint.waves ? n.hint.waves : 4;
   while (nw > 1 && fused_lds_bytes(n.D, n.L, n.k, nw) > (size_t)kMaxLdsBytes) nw >>= 1;
   return nw;
 }
@@ -111,8 +130,8 @@ bool staged_fits(const Norm& n) {
 // against 0.80 ms with 8 wavefronts on 256 streams of 16K rows).
 int split_nw(const Norm& n) {
   int nw = n.L >= 512 ? 8 : n.L >= 256 ? 4 : 2;
-  const int64_t t = g_tune[LAGKV_TUNE_WAVES];
-  if (t == 2 || t == 4 || t == 8) nw = (int)t;
+  const int t = n.hint.waves;
+  if (t == 2 || t == 4 || t == 8) nw = t;
   while (nw >= 2 && split_lds_bytes(n.D, n.esize, n.L, n.k, nw) > (size_t)80 * 1024) nw >>= 1;
   return nw >= 2 ? nw : 0;
 }
@@ -122,8 +141,8 @@ int split_nw(const Norm& n) {
 // every segment reads one extra chunk for its first reference), and segments keep >= 4 chunks.
 int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   int64_t nseg;
-  if (g_tune[LAGKV_TUNE_SEGMENTS]) {
-    nseg = g_tune[LAGKV_TUNE_SEGMENTS];
+  if (n.hint.nseg) {
+    nseg = n.hint.nseg;
   } else {
     const int64_t capacity = 256 * (nw >= 8 ? 2 : nw >= 4 ? 3 : 4);
     nseg = n.streams >= capacity ? 1 : (capacity + n.streams - 1) / n.streams;
@@ -135,8 +154,37 @@ int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   return (int)nseg;
 }
 
+// Segments of the register-resident kernel: one workgroup per CU is resident, so cut the
+// streams until there are a few workgroups per CU to balance the tail; every segment reads
+// one extra chunk, so segments keep at least 16 chunks.
+int pick_segments_hold(const Norm& n, int64_t n_s) {
+  int64_t nseg = n.hint.nseg;
+  if (!nseg) {
+    nseg = n.streams >= 1024 ? 1 : (1024 + n.streams - 1) / n.streams;
+    const int64_t cap = n_s / 16 > 1 ? n_s / 16 : 1;
+    if (nseg > cap) nseg = cap;
+  }
+  if (nseg > n_s) nseg = n_s;
+  return (int)(nseg < 1 ? 1 : nseg);
+}
+
+// Eq. 14-15 would need two passes over a chunk in the streaming kernel; the
+// register-resident kernel reads it once, so it is that variant's default where it applies.
+bool use_resident(const Norm& n) {
+  if (n.variant == LAGKV_SCORE_L2 || !hold_supported(n.D, n.esize, n.L, n.k)) return false;
+  return n.hint.path == LAGKV_PATH_RESIDENT || (n.hint.path == LAGKV_PATH_AUTO && n.variant == LAGKV_SCORE_LOCAL);
+}
+
 // Launch the one-shot fused kernel.
 int launch_fused_any(PassArgs& a, const Norm& n, hipStream_t s) {
+  a.order = n.hint.order;
+  a.sel = n.hint.sel;
+  if (use_resident(n)) {
+    a.nwaves = 8;
+    a.nseg = pick_segments_hold(n, a.n_s);
+    return launch_hold_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
+  }
+  if (n.hint.path == LAGKV_PATH_RESIDENT) return LAGKV_ESHAPE;
   a.nwaves = split_nw(n);
   a.nseg = pick_segments_split(n, a.n_s, a.nwaves);
   return launch_split_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
@@ -245,9 +293,7 @@ size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T) {
   if (validate(p, &n) != LAGKV_OK || T < 1 || T > kMaxRows) return 0;
   int64_t sb, sh, st;
   if (strides_of(p, n, T, &sb, &sh, &st) != LAGKV_OK) return 0;
-  // (the append of the L2 variant always takes the three-kernel path and needs its staging)
-  const bool fused = g_tune[LAGKV_TUNE_PATH] != 2 && shape_fused(n, sb, sh, st) && fused_fits(n) &&
-                     n.variant != LAGKV_SCORE_L2;
+  const bool fused = n.hint.path != LAGKV_PATH_STAGED && shape_fused(n, sb, sh, st) && fused_fits(n);
   if (fused) return 0;
   // one pass over T rows, and an append into a cache of capacity T
   lagkv_plan_t pl;
@@ -259,7 +305,7 @@ size_t lagkv_workspace_bytes(const lagkv_params* p, int64_t T) {
 
 int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T, float* scores,
                 void* ws, size_t ws_bytes, void* hip_stream) {
-  (void)ws;
+  (void)ws;  // no path stages anything for the scores alone
   (void)ws_bytes;
   Norm n;
   int rc = validate(p, &n);
@@ -278,11 +324,11 @@ int lagkv_score(const lagkv_params* p, const void* K, const void* V, int64_t T, 
   PassArgs a;
   fill_pass(&a, n, K, V, T, pl, sb, sh, st);
   a.scores = scores;
-  const int64_t force = g_tune[LAGKV_TUNE_PATH];
+  const int force = n.hint.path;
   const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, K, V, nullptr, nullptr);
-  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
-  if (fused_ok && force != 2) return launch_fused_any(a, n, s);
+  if ((force == LAGKV_PATH_FUSED || force == LAGKV_PATH_RESIDENT) && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != LAGKV_PATH_STAGED) return launch_fused_any(a, n, s);
   if (!staged_fits(n)) return LAGKV_ESHAPE;
   return hip_status(launch_staged_score(a, n.S, scores, s));
 }
@@ -305,6 +351,17 @@ int lagkv_select(const lagkv_params* p, const float* scores, int64_t T, int32_t*
 int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t T, void* K_out,
                    void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes,
                    void* hip_stream) {
+  return lagkv::compress_with_workspace(p, K, V, T, K_out, V_out, idx_out, scores_out, ws, ws_bytes,
+                                        hip_stream);
+}
+
+}  // extern "C"
+
+// The whole pass with the workspace given by the caller (lagkv_compress) or taken from the
+// library's static scratch (lagkv_compress_static).
+int lagkv::compress_with_workspace(const lagkv_params* p, const void* K, const void* V, int64_t T,
+                                   void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                                   void* ws, size_t ws_bytes, void* hip_stream) {
   Norm n;
   int rc = validate(p, &n);
   if (rc != LAGKV_OK) return rc;
@@ -335,11 +392,11 @@ int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t 
   a.V_out = (char*)V_out;
   a.idx_out = idx_out;
   a.scores = scores_out;
-  const int64_t force = g_tune[LAGKV_TUNE_PATH];
+  const int force = n.hint.path;
   const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, K, V, K_out, V_out);
-  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
-  if (fused_ok && force != 2) return launch_fused_any(a, n, s);
+  if ((force == LAGKV_PATH_FUSED || force == LAGKV_PATH_RESIDENT) && !fused_ok) return LAGKV_ESHAPE;
+  if (fused_ok && force != LAGKV_PATH_STAGED) return launch_fused_any(a, n, s);
   if (!staged_fits(n)) return LAGKV_ESHAPE;
   const StagedWs w = staged_ws(n, pl.n_scored, scores_out == nullptr);
   if (!ws || ws_bytes < w.total || !aligned_to(ws, 16)) return LAGKV_EWORKSPACE;
@@ -349,6 +406,31 @@ int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t 
   if (e == hipSuccess) e = launch_select(sc, n.streams, pl.n_scored, n.L, n.k, n.S, kept, s);
   if (e == hipSuccess) e = launch_staged_gather(a, kept, s);
   return hip_status(e);
+}
+
+extern "C" {
+
+int lagkv_cache_after_compress(const lagkv_params* p, int64_t T, lagkv_cache* c) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return rc;
+  if (!c) return LAGKV_EINVAL;
+  if (T < 0 || T > kMaxRows) return LAGKV_ESHAPE;
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  if (c->capacity < pl.T_out) return LAGKV_ECAPACITY;
+  // Eq. 12: the output is [sink | k rows per scored chunk | last chunk + remainder]
+  c->n_static = pl.n_scored > 0 ? n.S + (int64_t)n.k * pl.n_scored : (T < n.S ? T : n.S);
+  c->n_tail = pl.T_out - c->n_static;
+  c->n_seen = T;
+  return LAGKV_OK;
+}
+
+int64_t lagkv_prefill_rows(const lagkv_params* p, const lagkv_cache* c, int64_t rows_left) {
+  Norm n;
+  if (validate(p, &n) != LAGKV_OK || !c || rows_left <= 0) return 0;
+  const int64_t want = c->n_seen == 0 ? (int64_t)n.S + 2 * (int64_t)n.L : (int64_t)n.L;
+  return rows_left < want ? rows_left : want;
 }
 
 int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void* K_new,
@@ -383,12 +465,12 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
   const int64_t tail = total - base;
   const int64_t q = tail >= 2 * (int64_t)n.L ? tail / n.L - 1 : 0;
   hipStream_t s = (hipStream_t)hip_stream;
-  const int64_t force = g_tune[LAGKV_TUNE_PATH];
-  const bool fused_ok = n.variant != LAGKV_SCORE_L2 && shape_fused(n, sb, sh, st) && fused_fits(n) &&
+  const int force = n.hint.path;
+  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n) &&
                         fused_supported(n.D, n.esize, sb, sh, st, c->K, c->V, K_new, V_new);
-  if (force == 1 && !fused_ok) return LAGKV_ESHAPE;
+  if ((force == LAGKV_PATH_FUSED || force == LAGKV_PATH_RESIDENT) && !fused_ok) return LAGKV_ESHAPE;
   hipError_t e = hipSuccess;
-  if (fused_ok && force != 2) {
+  if (fused_ok && force != LAGKV_PATH_STAGED) {
     if (n_new > 0 || q > 0) {
       AppendArgs a;
       std::memset(&a, 0, sizeof(a));
@@ -416,9 +498,10 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
       a.f16 = n.f16;
       a.ddof = n.ddof;
       a.variant = n.variant;
+      a.sel = n.hint.sel;
       a.nwaves = pick_waves(n);
       // the single-round kernel serves the steady decode step unless a launch shape is forced
-      if (g_tune[LAGKV_TUNE_WAVES] == 0 && decode_step_supported(a)) e = launch_decode_step(a, s);
+      if (n.hint.waves == 0 && decode_step_supported(a)) e = launch_decode_step(a, s);
       else e = launch_fused_append(a, s);
     }
   } else {
@@ -487,14 +570,17 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* c, const void*
   return LAGKV_OK;
 }
 
-int lagkv_tune(int key, int64_t value) {
-  if (key < 0 || key >= LAGKV_TUNE_COUNT || value < 0) return LAGKV_EINVAL;
-  if (key == LAGKV_TUNE_PATH && value > 2) return LAGKV_EINVAL;
-  if (key == LAGKV_TUNE_WAVES && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-    return LAGKV_EINVAL;
-  if (key == LAGKV_TUNE_SEGMENTS && value > (1 << 20)) return LAGKV_EINVAL;
-  g_tune[key] = value;
-  return LAGKV_OK;
+int32_t lagkv_launch_hint(int path, int waves, int segments) {
+  if (path < 0 || path > LAGKV_PATH_RESIDENT || segments < 0 || segments > kMaxSegments) return -1;
+  if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return -1;
+  return (int32_t)(path | (waves << kHintWavesShift) | (segments << kHintSegShift));
+}
+
+int32_t lagkv_launch_hint_ex(int path, int waves, int segments, int order, int select) {
+  const int32_t base = lagkv_launch_hint(path, waves, segments);
+  if (base < 0 || order < 0 || order > LAGKV_ORDER_BITREV || select < 0 || select > LAGKV_SELECT_GROUP)
+    return -1;
+  return base | (order << kHintOrderShift) | (select << kHintSelShift);
 }
 
 const char* lagkv_strerror(int status) {
@@ -510,6 +596,6 @@ const char* lagkv_strerror(int status) {
   }
 }
 
-int lagkv_version(void) { return 100; }
+int lagkv_version(void) { return 200; }
 
 }  // extern "C"

@@ -5,7 +5,14 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "lagkv.h"
+
 namespace lagkv {
+
+// lagkv_compress with an explicit workspace (defined in lagkv_api.hip).
+int compress_with_workspace(const lagkv_params* p, const void* K, const void* V, int64_t T,
+                            void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
+                            size_t ws_bytes, void* hip_stream);
 
 // One compression pass over [streams] caches.  Strides are in BYTES here.
 struct PassArgs {
@@ -25,9 +32,34 @@ struct PassArgs {
   int32_t f16;         // 2-byte elements are IEEE binary16 (else bfloat16)
   int32_t ddof;
   int32_t variant;
-  int32_t nseg;        // segments per stream (fused kernel)
-  int32_t nwaves;      // wavefronts per workgroup (fused kernel)
+  int32_t nseg;        // segments each stream is cut into (one-shot kernels)
+  int32_t nwaves;      // wavefronts per workgroup (one-shot kernels)
+  int32_t order;       // workgroup -> stream order (see stream_of)
+  int32_t sel;         // selection mode (see wg_select.hpp)
 };
+
+// Which of n streams the i-th workgroup (or group of segment workgroups) takes.
+//   0  i                               consecutive workgroups take consecutive streams
+//   1  even streams first, then odd    the workgroups resident at one time span the whole tensor
+//   2  i % 8 picks one eighth of the streams (n divisible by 8): workgroups are dealt to the
+//      eight XCDs round-robin, so every XCD's L2 then sees one contiguous eighth
+//   3  bit reversal of i (n a power of two): neighbours in time are far apart in memory
+// Every order is a permutation of [0, n); orders whose precondition fails fall back to 0.
+__host__ __device__ inline int64_t stream_of(int64_t i, int64_t n, int order) {
+  if (order == 1) {
+    const int64_t half = (n + 1) / 2;
+    return i < half ? 2 * i : 2 * (i - half) + 1;
+  }
+  if (order == 2 && n % 8 == 0) return (i % 8) * (n / 8) + i / 8;
+  if (order == 3 && n > 1 && (n & (n - 1)) == 0) {
+    int bits = 0;
+    while ((int64_t(1) << bits) < n) ++bits;
+    int64_t r = 0;
+    for (int b = 0; b < bits; ++b) r |= ((i >> b) & 1) << (bits - 1 - b);
+    return r;
+  }
+  return i;
+}
 
 // In-place append + recursive compression of [streams] dense caches.
 struct AppendArgs {
@@ -47,6 +79,7 @@ struct AppendArgs {
   int32_t S, L, k;
   int32_t esize, f16, ddof, variant;
   int32_t nwaves;
+  int32_t sel;         // selection mode (see wg_select.hpp)
 };
 
 // True when the fused kernels can serve this row size / alignment.
@@ -57,6 +90,10 @@ size_t fused_lds_bytes(int D, int L, int k, int nwaves);
 // One-shot fused kernel (tensor-split streaming): nwaves in {2,4,8}.
 size_t split_lds_bytes(int D, int esize, int L, int k, int nwaves);
 hipError_t launch_split_pass(const PassArgs& a, hipStream_t s);
+
+// One-shot register-resident kernel (every row read once): 256-byte rows, L in {128, 256, 512}.
+bool hold_supported(int D, int esize, int L, int k);
+hipError_t launch_hold_pass(const PassArgs& a, hipStream_t s);
 
 hipError_t launch_fused_append(const AppendArgs& a, hipStream_t s);
 // Single-round decode step (exactly one chunk completes; no intermediate append copy).

@@ -106,6 +106,15 @@ struct TStats {  // running per-channel min/max of the lane's VEC channels (Eq. 
   }
 };
 
+// Makes the running statistics materialise where this is called.  Without it the compiler
+// is free to postpone the whole min/max chain of an unrolled sweep to the point where its
+// result is used, which keeps the unpacked rows of the entire sweep alive in registers.
+template <int VEC>
+__device__ __forceinline__ void pin(TStats<VEC>& s) {
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) asm volatile("" : "+v"(s.mn[j]), "+v"(s.mx[j]));
+}
+
 template <int VEC>
 struct TRef {  // reference statistics as Eq. 9 consumes them: zbar = (x - mn) * iv
   float mn[VEC], iv[VEC];

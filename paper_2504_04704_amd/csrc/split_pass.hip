@@ -1,9 +1,9 @@
 // Tensor-split streaming LagKV kernel for gfx950 (the default one-shot kernel).
 //
-// Like the streaming kernel in fused_pass.hip a workgroup walks a segment of one
-// stream backwards and scores chunk p with the statistics of chunk p+1 while folding
-// chunk p's own min/max for chunk p-1, so every input byte is streamed once.  Here the
-// first half of the wavefronts handles only K rows and the second half only V rows:
+// A workgroup walks a segment of one stream backwards and scores chunk p with the
+// statistics of chunk p+1 while folding chunk p's own min/max for chunk p-1, so every
+// input byte is streamed once.  The first half of the wavefronts handles only K rows and
+// the second half only V rows:
 // a lane carries the statistics of ONE tensor, which halves the register footprint and
 // lets 16 wavefronts share a CU (4 per SIMD) with eight 16-byte loads in flight each.
 // The kept rows are re-read for the compaction right after the selection; the chunks
@@ -13,6 +13,7 @@
 #include "lds_dma.hpp"
 #include "row_ops.hpp"
 #include "wave_ops.hpp"
+#include "wg_select.hpp"
 
 #ifndef LAGKV_SPLIT_U
 #define LAGKV_SPLIT_U 4      // rows in flight per lane
@@ -33,7 +34,7 @@
 namespace lagkv {
 
 struct SplitLds {
-  int off_vK, off_vV, off_list, off_stat, off_ring, total;  // bytes
+  int off_vK, off_vV, off_list, off_sel, off_stat, off_ring, total;  // bytes
 };
 __host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw, bool ring) {
   SplitLds l;
@@ -41,7 +42,8 @@ __host__ __device__ inline SplitLds split_lds(int D, int L, int k, int nw, bool 
   l.off_vK = 0;
   l.off_vV = lp * 4;
   l.off_list = 2 * lp * 4;
-  l.off_stat = l.off_list + kp * 4;
+  l.off_sel = l.off_list + kp * 4;              // scratch of the workgroup-wide selection
+  l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;
   l.off_ring = (l.off_stat + nw * 2 * D * 4 + 1023) & ~1023;  // [wave][mn|mx][D], then the rings
   l.total = ring ? l.off_ring + nw * kRing * 1024 : l.off_stat + nw * 2 * D * 4;
   return l;
@@ -65,6 +67,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
   float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
   uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
+  uint32_t* selbuf = reinterpret_cast<uint32_t*>(lds + lay.off_sel);
   float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
 
   const int tensor = wave >= G ? 1 : 0;  // 0: this wavefront handles K rows, 1: V rows
@@ -77,7 +80,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const int64_t rowbytes = (int64_t)LPR * 16;
   const int64_t coff = (int64_t)cl * 16;
 
-  const int64_t stream = blockIdx.x / a.nseg;
+  const int64_t stream = stream_of(blockIdx.x / a.nseg, (int64_t)a.B * a.H, a.order);
   const int seg = blockIdx.x % a.nseg;
   const int64_t b = stream / a.H, h = stream % a.H;
   const char* kin = a.K + b * a.sb + h * a.sh;
@@ -294,6 +297,17 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         iout[S + p * k + i] = (int32_t)(S + p * L + list[i]);
   };
 
+  // Eq. 10-11 and the top-k of chunk p from the variances in vK / vV (visible to all).
+  // Selection by all wavefronts needs one token per thread; otherwise one wavefront does
+  // it, a different one for every chunk so that the work is spread over the SIMDs.
+  const bool group_sel = a.sel == kSelGroup && L <= nthreads;
+  auto select = [&](int64_t p) __attribute__((always_inline)) {
+    float* g = sout ? sout + p * L : nullptr;
+    if (group_sel) group_score_select(vK, vV, L, k, gather, g, selbuf, list, nullptr, tid, nthreads);
+    else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0))
+      wave_score_select_lean(vK, vV, L, k, gather, g, list, nullptr, lane);
+  };
+
   if (a.variant == 2) {
     // Eq. 16: score = -||K_t||_2.  No reference and no softmax; V is read only where it is kept.
     // All wavefronts share the K rows of the chunk.
@@ -320,10 +334,12 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
           if (cl == 0 && r[u] < L) vK[r[u]] = -sqrtf(ss);
         }
       }
+      if (group_sel) group_sel_clear(selbuf, tid, nthreads);
       __syncthreads();
-      if (wave == 0) wave_topk_scores(vK, L, k, list, lane);
       if (sout)
         for (int i = tid; i < L; i += nthreads) sout[p * L + i] = vK[i];
+      if (group_sel) group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
+      else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) wave_topk_scores(vK, L, k, list, lane);
       __syncthreads();
       if (gather) compact(p);
     }
@@ -339,8 +355,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
       ref.from(acc);
       scan(crow, LAGKV_LOCAL_REV != 0, F_{}, T_{});
       __syncthreads();
-      if (wave == 0)
-        wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
+      select(p);
       __syncthreads();
       if (gather) compact(p);
     }
@@ -359,8 +374,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     fold();  // barrier inside: the variances are visible
     ref.from(acc);  // chunk p is the reference of chunk p-1 (done before the selection so
                     // that the running statistics are dead across it: fewer live registers)
-    if (wave == 0)
-      wave_score_select_lean(vK, vV, L, k, gather, sout ? sout + p * L : nullptr, list, nullptr, lane);
+    select(p);
     __syncthreads();
     if (gather) compact(p);
   }

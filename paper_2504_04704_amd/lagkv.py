@@ -2,7 +2,7 @@
 
 Argument marshalling only: every step of the pass runs in the HIP kernels.
 Functions carry the C names (`plan`, `workspace_bytes`, `score`, `select`,
-`compress`, `append_and_compress`, `tune`).  torch is used for device memory
+`compress`, `append_and_compress`, `launch_hint`, ...).  torch is used for device memory
 and the current HIP stream; there is no CPU fallback: if the library is
 missing or a call fails, an exception is raised.
 """
@@ -21,12 +21,14 @@ _lib = None
 OK, EINVAL, ESHAPE, EDTYPE, ECAPACITY, EWORKSPACE, EHIP = range(7)
 F32, BF16, F16 = 0, 1, 2
 SCORE_LAG, SCORE_LOCAL, SCORE_L2 = 0, 1, 2
-TUNE_PATH, TUNE_WAVES, TUNE_SEGMENTS = 0, 1, 2
-PATH_AUTO, PATH_FUSED, PATH_STAGED = 0, 1, 2
+PATH_AUTO, PATH_FUSED, PATH_STAGED, PATH_RESIDENT = 0, 1, 2, 3
+ORDER_LINEAR, ORDER_EVEN_ODD, ORDER_XCD, ORDER_BITREV = 0, 1, 2, 3
+SELECT_AUTO, SELECT_WAVE, SELECT_GROUP = 0, 1, 2
 
 EXPORTS = ("lagkv_plan", "lagkv_keep_for_compression", "lagkv_workspace_bytes", "lagkv_score",
-           "lagkv_select", "lagkv_compress", "lagkv_append_and_compress", "lagkv_tune",
-           "lagkv_strerror", "lagkv_version")
+           "lagkv_select", "lagkv_compress", "lagkv_cache_after_compress", "lagkv_prefill_rows",
+           "lagkv_append_and_compress", "lagkv_launch_hint", "lagkv_launch_hint_ex", "lagkv_strerror",
+           "lagkv_version")
 
 
 class LagKVError(RuntimeError):
@@ -40,7 +42,7 @@ class Params(C.Structure):
                 ("S", C.c_int32), ("L", C.c_int32),
                 ("r", C.c_double),
                 ("dtype", C.c_int32), ("variant", C.c_int32), ("std_ddof", C.c_int32),
-                ("reserved", C.c_int32),
+                ("launch", C.c_int32),
                 ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64)]
 
 
@@ -85,8 +87,14 @@ def load():
     lib.lagkv_append_and_compress.argtypes = [C.POINTER(Params), C.POINTER(CacheT), vp, vp, i64, vp,
                                               sz, vp]
     lib.lagkv_append_and_compress.restype = C.c_int
-    lib.lagkv_tune.argtypes = [C.c_int, i64]
-    lib.lagkv_tune.restype = C.c_int
+    lib.lagkv_cache_after_compress.argtypes = [C.POINTER(Params), i64, C.POINTER(CacheT)]
+    lib.lagkv_cache_after_compress.restype = C.c_int
+    lib.lagkv_prefill_rows.argtypes = [C.POINTER(Params), C.POINTER(CacheT), i64]
+    lib.lagkv_prefill_rows.restype = C.c_int64
+    lib.lagkv_launch_hint.argtypes = [C.c_int, C.c_int, C.c_int]
+    lib.lagkv_launch_hint.restype = C.c_int32
+    lib.lagkv_launch_hint_ex.argtypes = [C.c_int] * 5
+    lib.lagkv_launch_hint_ex.restype = C.c_int32
     lib.lagkv_strerror.argtypes = [C.c_int]
     lib.lagkv_strerror.restype = C.c_char_p
     lib.lagkv_version.argtypes = []
@@ -111,14 +119,25 @@ def _check(status: int, where: str):
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
 
+def launch_hint(path: int = PATH_AUTO, waves: int = 0, segments: int = 0, order: int = 0,
+                select: int = 0) -> int:
+    """lagkv_launch_hint(_ex): the value of Params.launch that overrides the launch choice of one call."""
+    v = load().lagkv_launch_hint_ex(path, waves, segments, order, select) if (order or select) \
+        else load().lagkv_launch_hint(path, waves, segments)
+    if v < 0:
+        raise LagKVError(EINVAL, "lagkv_launch_hint")
+    return v
+
+
 def make_params(B: int, H: int, D: int, S: int, L: int, r: float, dtype=BF16, variant=SCORE_LAG,
-                std_ddof: int = 1, strides: Tuple[int, int, int] = (0, 0, 0)) -> Params:
+                std_ddof: int = 1, strides: Tuple[int, int, int] = (0, 0, 0), launch: int = 0) -> Params:
     if isinstance(dtype, torch.dtype):
         dtype = _DTYPES[dtype]
-    return Params(B, H, D, S, L, float(r), dtype, variant, std_ddof, 0, *strides)
+    return Params(B, H, D, S, L, float(r), dtype, variant, std_ddof, launch, *strides)
 
 
-def params_for(K: torch.Tensor, S: int, L: int, r: float, variant=SCORE_LAG, std_ddof: int = 1) -> Params:
+def params_for(K: torch.Tensor, S: int, L: int, r: float, variant=SCORE_LAG, std_ddof: int = 1,
+               launch: int = 0) -> Params:
     """Parameters for a [B,H,T,D] tensor (any strides with a contiguous channel axis)."""
     if K.dim() != 4 or K.stride(3) != 1:
         raise ValueError("expected a [B,H,T,D] tensor with contiguous channels")
@@ -126,7 +145,7 @@ def params_for(K: torch.Tensor, S: int, L: int, r: float, variant=SCORE_LAG, std
         raise TypeError(f"unsupported dtype {K.dtype}")
     B, H, _, D = K.shape
     return make_params(B, H, D, S, L, r, _DTYPES[K.dtype], variant, std_ddof,
-                       (K.stride(0), K.stride(1), K.stride(2)))
+                       (K.stride(0), K.stride(1), K.stride(2)), launch)
 
 
 def plan(p: Params, T: int, n_static: int = -1) -> PlanT:
@@ -145,10 +164,6 @@ def keep_for_compression(T: int, S: int, L: int, ratio: float) -> Tuple[int, flo
 
 def workspace_bytes(p: Params, T: int) -> int:
     return int(load().lagkv_workspace_bytes(C.byref(p), T))
-
-
-def tune(key: int, value: int) -> None:
-    _check(load().lagkv_tune(key, value), "lagkv_tune")
 
 
 def _stream_ptr(device) -> int:
@@ -170,18 +185,16 @@ def _same_layout(K: torch.Tensor, V: torch.Tensor):
 
 
 def score(K: torch.Tensor, V: Optional[torch.Tensor], S: int, L: int, r: float, variant=SCORE_LAG,
-          std_ddof: int = 1, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+          std_ddof: int = 1, ws: Optional[torch.Tensor] = None, launch: int = 0) -> torch.Tensor:
     """lagkv_score: fp32 scores [B,H,n_scored*L] of every scored chunk."""
     if not K.is_cuda:
         raise RuntimeError("lagkv.score needs device tensors; there is no CPU path")
     if V is not None:
         _same_layout(K, V)
-    p = params_for(K, S, L, r, variant, std_ddof)
+    p = params_for(K, S, L, r, variant, std_ddof, launch)
     T = K.shape[2]
     pl = plan(p, T)
     out = torch.empty((p.B, p.H, pl.n_scored * L), dtype=torch.float32, device=K.device)
-    if ws is None:
-        ws = _workspace(p, T, K.device)
     _check(load().lagkv_score(C.byref(p), K.data_ptr(), _ptr(V), T, out.data_ptr(), _ptr(ws),
                               0 if ws is None else ws.numel(), _stream_ptr(K.device)), "lagkv_score")
     return out
@@ -217,12 +230,12 @@ def compress(K: torch.Tensor, V: torch.Tensor, S: int, L: int, r: float, variant
              std_ddof: int = 1, want_idx: bool = True, want_scores: bool = False,
              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
              idx_out: Optional[torch.Tensor] = None, scores_out: Optional[torch.Tensor] = None,
-             ws: Optional[torch.Tensor] = None) -> Compressed:
+             ws: Optional[torch.Tensor] = None, launch: int = 0) -> Compressed:
     """lagkv_compress: one whole pass.  Output buffers may be passed in (benchmarks)."""
     if not K.is_cuda:
         raise RuntimeError("lagkv.compress needs device tensors; there is no CPU path")
     _same_layout(K, V)
-    p = params_for(K, S, L, r, variant, std_ddof)
+    p = params_for(K, S, L, r, variant, std_ddof, launch)
     B, H, T, D = K.shape
     pl = plan(p, T)
     if out is None:
@@ -252,8 +265,9 @@ class Cache:
 
     def __init__(self, B: int, H: int, D: int, capacity: int, S: int, L: int, r: float,
                  dtype=torch.bfloat16, device="cuda", variant=SCORE_LAG, std_ddof: int = 1,
-                 track_positions: bool = True):
+                 track_positions: bool = True, launch: int = 0):
         self.S, self.L, self.r, self.variant, self.std_ddof = S, L, r, variant, std_ddof
+        self.launch = launch
         self.K = torch.empty((B, H, capacity, D), dtype=dtype, device=device)
         self.V = torch.empty_like(self.K)
         self.pos = torch.empty((B, H, capacity), dtype=torch.int32, device=device) \
@@ -263,22 +277,27 @@ class Cache:
 
     @classmethod
     def from_compressed(cls, comp: Compressed, T: int, capacity: int, S: int, L: int, r: float,
-                        variant=SCORE_LAG, std_ddof: int = 1) -> "Cache":
+                        variant=SCORE_LAG, std_ddof: int = 1, launch: int = 0) -> "Cache":
         """Cache holding the output of compress() on T rows, with room to grow."""
         B, H, T_out, D = comp.K.shape
         c = cls(B, H, D, capacity, S, L, r, comp.K.dtype, comp.K.device, variant, std_ddof,
-                comp.idx is not None)
+                comp.idx is not None, launch)
         c.K[:, :, :T_out].copy_(comp.K)
         c.V[:, :, :T_out].copy_(comp.V)
         if comp.idx is not None:
             c.pos[:, :, :T_out].copy_(comp.idx)
-        k, n_s = comp.plan.k, comp.plan.n_scored
-        if n_s > 0:
-            c.c.n_static, c.c.n_tail = S + k * n_s, T_out - (S + k * n_s)
-        else:
-            c.c.n_static, c.c.n_tail = min(T, S), T - min(T, S)
-        c.c.n_seen = T
+        c.mark_compressed(T)
         return c
+
+    def _params(self, strides=(0, 0, 0)) -> Params:
+        B, H, _, D = self.K.shape
+        return make_params(B, H, D, self.S, self.L, self.r, _DTYPES[self.K.dtype], self.variant,
+                           self.std_ddof, strides, self.launch)
+
+    def mark_compressed(self, T: int) -> None:
+        """lagkv_cache_after_compress: the buffers now hold the output of compress() on T rows."""
+        _check(load().lagkv_cache_after_compress(C.byref(self._params()), T, C.byref(self.c)),
+               "lagkv_cache_after_compress")
 
     @property
     def n_static(self) -> int:
@@ -307,8 +326,7 @@ class Cache:
                 raise ValueError("K_new must be [B,H,n_new,D] of the cache dtype")
             n_new = K_new.shape[2]
             strides = (K_new.stride(0), K_new.stride(1), K_new.stride(2))
-        p = make_params(B, H, D, self.S, self.L, self.r, _DTYPES[self.K.dtype], self.variant,
-                        self.std_ddof, strides)
+        p = self._params(strides)
         need = workspace_bytes(p, cap)
         if need and (self._ws is None or self._ws.numel() < need):
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.K.device)
@@ -325,13 +343,12 @@ class Cache:
         each slice between the calls is the caller's; here the rows are given.  Returns the
         number of calls made."""
         T = K.shape[2]
-        first = min(T, self.S + 2 * self.L) if self.n_seen == 0 else 0
+        p = self._params()
         calls, t = 0, 0
-        if first:
-            self.append_and_compress(K[:, :, :first], V[:, :, :first])
-            calls, t = 1, first
         while t < T:
-            n = min(self.L, T - t)
+            n = load().lagkv_prefill_rows(C.byref(p), C.byref(self.c), T - t)
+            if n <= 0:
+                raise LagKVError(EINVAL, "lagkv_prefill_rows")
             self.append_and_compress(K[:, :, t:t + n], V[:, :, t:t + n])
             t += n
             calls += 1

@@ -135,7 +135,9 @@ def test_parameter_validation(lib):
     assert _status(lagkv.plan, P(), -5) == lagkv.ESHAPE
     assert lib.lagkv_plan(None, 10, -1, C.byref(lagkv.PlanT())) == lagkv.EINVAL
     assert lib.lagkv_plan(C.byref(P()), 10, -1, None) == lagkv.EINVAL
-    p = P(); p.reserved = 1
+    p = P(); p.launch = -1
+    assert _status(lagkv.plan, p, 1024) == lagkv.EINVAL
+    p = P(); p.launch = 3 << 2            # 3 wavefronts: not a value lagkv_launch_hint returns
     assert _status(lagkv.plan, p, 1024) == lagkv.EINVAL
 
 
@@ -162,12 +164,14 @@ def test_calls_reject_bad_arguments_before_touching_the_device(lib):
     assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, fake, 64,
                               None) == lagkv.EWORKSPACE
     # forcing the fused kernels on a shape they do not cover is an error, not a fallback
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
-    try:
-        assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, fake, need,
-                                  None) == lagkv.ESHAPE
-    finally:
-        lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
+    forced = lagkv.make_params(1, 2, 40, 16, 128, 0.5, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))
+    assert lib.lagkv_compress(C.byref(forced), fake, fake, 1024, fake, fake, None, None, fake, need,
+                              None) == lagkv.ESHAPE
+    # the staged path asked for by hint needs its workspace even on a fused shape, and says so
+    staged = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_STAGED))
+    assert lagkv.workspace_bytes(staged, 1024) > 0
+    assert lib.lagkv_compress(C.byref(staged), fake, fake, 1024, fake, fake, None, None, None, 0,
+                              None) == lagkv.EWORKSPACE
     # L beyond what fits the per-workgroup LDS budget
     huge = lagkv.make_params(1, 1, 64, 0, 1 << 20, 0.5, lagkv.F32)
     assert lib.lagkv_score(C.byref(huge), fake, fake, 1 << 22, fake, None, 0, None) == lagkv.ESHAPE
@@ -187,15 +191,68 @@ def test_append_validation(lib):
     assert lib.lagkv_append_and_compress(C.byref(p), C.byref(c2), fake, fake, 4, None, 0, None) == lagkv.EINVAL
 
 
-def test_tune_and_strerror(lib):
-    assert _status(lagkv.tune, 99, 1) == lagkv.EINVAL
-    assert _status(lagkv.tune, lagkv.TUNE_WAVES, 3) == lagkv.EINVAL
-    assert _status(lagkv.tune, lagkv.TUNE_PATH, 3) == lagkv.EINVAL
-    lagkv.tune(lagkv.TUNE_WAVES, 8); lagkv.tune(lagkv.TUNE_WAVES, 0)
+def test_launch_hint_is_a_pure_function(lib):
+    """lagkv_launch_hint(_ex) packs its arguments, rejects unknown values, and a call with the
+    hint behaves the same however often and in whatever order hints were made (no state)."""
+    assert lib.lagkv_launch_hint(0, 0, 0) == 0 and lib.lagkv_launch_hint_ex(0, 0, 0, 0, 0) == 0
+    seen = set()
+    for path in range(4):
+        for waves in (0, 1, 2, 4, 8):
+            for seg in (0, 1, 7, 1 << 20):
+                v = lib.lagkv_launch_hint(path, waves, seg)
+                assert v >= 0 and v == lib.lagkv_launch_hint(path, waves, seg) and v not in seen
+                seen.add(v)
+                for order in range(4):
+                    for sel in range(3):
+                        w = lib.lagkv_launch_hint_ex(path, waves, seg, order, sel)
+                        assert w >= 0 and (w == v) == (order == 0 and sel == 0)
+                        assert _status(lagkv.plan, lagkv.make_params(1, 2, 64, 16, 128, 0.5, launch=w), 1024) == lagkv.OK
+    for bad in [(4, 0, 0), (-1, 0, 0), (0, 3, 0), (0, 16, 0), (0, 0, -1), (0, 0, (1 << 20) + 1)]:
+        assert lib.lagkv_launch_hint(*bad) == -1
+    assert lib.lagkv_launch_hint_ex(0, 0, 0, 4, 0) == -1 and lib.lagkv_launch_hint_ex(0, 0, 0, 0, 3) == -1
+    # making other hints in between changes nothing for a call that carries its own
+    staged = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_STAGED))
+    before = lagkv.workspace_bytes(staged, 4096)
+    lagkv.launch_hint(lagkv.PATH_FUSED, 8, 5)
+    assert lagkv.workspace_bytes(staged, 4096) == before > 0
+    assert lagkv.workspace_bytes(lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32), 4096) == 0
+
+
+def test_cache_after_compress_and_prefill_rows_follow_eq12(lib):
+    """The host calls that keep the partition integers behind the ABI, against the oracle's plan."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        S = int(rng.integers(0, 40)); L = int(rng.integers(1, 200)); k = int(rng.integers(1, L + 1))
+        T = int(rng.integers(0, 4000)); r = (k + 0.5) / L if k < L else 1.0
+        p = lagkv.make_params(2, 3, 8, S, L, r)
+        want = O.plan(T, S, L, r)
+        c = lagkv.CacheT(0x1000, 0x1000, None, want["T_out"] + int(rng.integers(0, 3)), 7, 7, 7)
+        assert lib.lagkv_cache_after_compress(C.byref(p), T, C.byref(c)) == lagkv.OK
+        if want["n_scored"]:
+            assert (c.n_static, c.n_tail, c.n_seen) == (S + k * want["n_scored"], L + want["rem"], T)
+        else:
+            assert (c.n_static, c.n_tail, c.n_seen) == (min(T, S), T - min(T, S), T)
+        assert c.n_static + c.n_tail == want["T_out"]
+        # chunk-by-chunk prefill: S + 2L rows first, then one lag per call
+        empty = lagkv.CacheT(0x1000, 0x1000, None, 10, 0, 0, 0)
+        assert lib.lagkv_prefill_rows(C.byref(p), C.byref(empty), 10**9) == S + 2 * L
+        assert lib.lagkv_prefill_rows(C.byref(p), C.byref(empty), 5) == min(5, S + 2 * L)
+        assert lib.lagkv_prefill_rows(C.byref(p), C.byref(c), 10**9) == (L if T > 0 else S + 2 * L)
+        assert lib.lagkv_prefill_rows(C.byref(p), C.byref(c), 0) == 0
+    p = lagkv.make_params(1, 1, 8, 16, 128, 0.25)
+    small = lagkv.CacheT(0x1000, 0x1000, None, 100, 0, 0, 0)
+    assert lib.lagkv_cache_after_compress(C.byref(p), 4096, C.byref(small)) == lagkv.ECAPACITY
+    assert (small.n_static, small.n_tail, small.n_seen) == (0, 0, 0)
+    assert lib.lagkv_cache_after_compress(C.byref(p), 4096, None) == lagkv.EINVAL
+    assert lib.lagkv_cache_after_compress(None, 4096, C.byref(small)) == lagkv.EINVAL
+    assert lib.lagkv_prefill_rows(None, C.byref(small), 5) == 0
+
+
+def test_strerror_and_version(lib):
     for s in range(7):
         assert len(lagkv.strerror(s)) > 1
     assert lagkv.strerror(1234) == "unknown status"
-    assert lagkv.version() >= 100
+    assert lagkv.version() >= 200
 
 
 def test_binding_refuses_cpu_tensors():

@@ -23,11 +23,14 @@ def say(*a):
 
 
 @pytest.fixture(autouse=True)
-def _reset_tuning():
+def _library():
     lagkv.load()
     yield
-    for key in (lagkv.TUNE_PATH, lagkv.TUNE_WAVES, lagkv.TUNE_SEGMENTS):
-        lagkv.tune(key, 0)
+
+
+def hint(path=lagkv.PATH_AUTO, waves=0, segments=0, order=0, select=0):
+    """Launch override of one call (a pure function of its arguments; the library keeps no state)."""
+    return lagkv.launch_hint(path, waves, segments, order, select)
 
 
 def gen(B, H, T, D, dtype, seed, device=DEV):
@@ -39,8 +42,8 @@ def gen(B, H, T, D, dtype, seed, device=DEV):
     return K, V
 
 
-def run_and_check(K, V, S, L, r, variant=lagkv.SCORE_LAG, ddof=1, streams=None):
-    out = lagkv.compress(K, V, S, L, r, variant=variant, std_ddof=ddof, want_scores=True)
+def run_and_check(K, V, S, L, r, variant=lagkv.SCORE_LAG, ddof=1, streams=None, launch=0):
+    out = lagkv.compress(K, V, S, L, r, variant=variant, std_ddof=ddof, want_scores=True, launch=launch)
     torch.cuda.synchronize()
     B, H, T, D = K.shape
     rep = PU.StreamReport()
@@ -58,8 +61,7 @@ def test_config1_tiny_fp32(path):
     cfg = synth.CONFIGS["cfg1_tiny_f32"]
     say("config 1", cfg, "path", path)
     K, V = synth.make_kv(cfg, device=DEV)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    out, rep = run_and_check(K, V, cfg.S, cfg.L, cfg.r)
+    out, rep = run_and_check(K, V, cfg.S, cfg.L, cfg.r, launch=hint(path))
     assert out.plan.T_out == 640 and rep.chunks == 12
     say("config 1 ok: flipped", rep.flipped_chunks, "max score rel", rep.max_score_rel)
 
@@ -92,8 +94,7 @@ def test_shapes_against_oracle(shape, path):
     B, H, T, D, dtype, S, L, r = shape
     say("shape", shape, "path", path)
     K, V = gen(B, H, T, D, dtype, seed=hash(shape[:4]) & 0xffff)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    out, rep = run_and_check(K, V, S, L, r)
+    out, rep = run_and_check(K, V, S, L, r, launch=hint(path))
     assert out.plan.T_out == O.plan(T, S, L, r)["T_out"]
     say("ok: chunks", rep.chunks, "flipped", rep.flipped_chunks, "max rel", rep.max_score_rel)
 
@@ -112,10 +113,89 @@ def test_unaligned_head_dims_use_the_staged_path(D, dtype):
 def test_launch_shapes_agree(nw, nseg):
     say("launch shape nw", nw, "nseg", nseg)
     K, V = gen(2, 2, 16 + 9 * 96 + 50, 128, torch.bfloat16, seed=5)
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
-    lagkv.tune(lagkv.TUNE_WAVES, nw)
-    lagkv.tune(lagkv.TUNE_SEGMENTS, nseg)
-    run_and_check(K, V, 16, 96, 0.25)
+    run_and_check(K, V, 16, 96, 0.25, launch=hint(lagkv.PATH_FUSED, nw, nseg))
+
+
+@pytest.mark.parametrize("order", [lagkv.ORDER_EVEN_ODD, lagkv.ORDER_XCD, lagkv.ORDER_BITREV])
+@pytest.mark.parametrize("B,H", [(2, 4), (3, 1), (1, 5)])
+def test_stream_orders_agree(order, B, H):
+    """Every workgroup-to-stream order is a permutation: same result as the linear one (8, 3 and 5
+    streams: multiple of 8 and power of two, odd, neither)."""
+    say("stream order", order, B, H)
+    K, V = gen(B, H, 16 + 6 * 64 + 9, 128, torch.bfloat16, seed=17)
+    for path in (lagkv.PATH_FUSED, lagkv.PATH_RESIDENT):
+        L = 128 if path == lagkv.PATH_RESIDENT else 64
+        ref = lagkv.compress(K, V, 16, L, 0.25, launch=hint(path))
+        out = lagkv.compress(K, V, 16, L, 0.25, launch=hint(path, segments=2, order=order))
+        torch.cuda.synchronize()
+        assert torch.equal(out.idx, ref.idx) and torch.equal(out.K, ref.K) and torch.equal(out.V, ref.V)
+
+
+@pytest.mark.parametrize("select", [lagkv.SELECT_WAVE, lagkv.SELECT_GROUP])
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
+@pytest.mark.parametrize("L,r,nw", [(512, 0.25, 8), (128, 0.25, 2), (256, 0.125, 4), (100, 0.33, 2), (24, 0.5, 8),
+                                    (96, 0.99, 4), (64, 0.02, 1), (300, 0.1, 4)])
+def test_selection_modes_against_oracle(select, variant, L, r, nw):
+    """Selection by one (rotating) wavefront and by all wavefronts (digit histograms), incl. a lag
+    with more tokens than threads (falls back to one wavefront), k = 1 and k = L - 1."""
+    say("selection mode", select, "variant", variant, "L", L, "r", r, "waves", nw)
+    K, V = gen(1, 3, 16 + 5 * L + 7, 128, torch.bfloat16, seed=L + select)
+    K[0, 1, 16 + 5] = K[0, 1, 16 + 2]; V[0, 1, 16 + 5] = V[0, 1, 16 + 2]     # an exact tie
+    run_and_check(K, V, 16, L, r, variant=variant, launch=hint(lagkv.PATH_FUSED, nw, 2, select=select))
+
+
+def test_group_selection_with_many_ties():
+    """Whole chunks of identical rows (every score tied) and rows duplicated in blocks: the
+    histogram selection must admit ties from the lowest position up, exactly as the oracle."""
+    say("group selection, ties")
+    L, S = 256, 8
+    K, V = gen(1, 2, S + 4 * L, 128, torch.bfloat16, seed=33)
+    K[0, 0, S:S + L] = K[0, 0, S]; V[0, 0, S:S + L] = V[0, 0, S]              # chunk 0 of head 0: all tied
+    K[0, 1, S + L:S + 2 * L:2] = K[0, 1, S + L + 1:S + 2 * L:2]               # pairs of equal rows
+    V[0, 1, S + L:S + 2 * L:2] = V[0, 1, S + L + 1:S + 2 * L:2]
+    for variant in (lagkv.SCORE_LAG, lagkv.SCORE_L2):
+        out, _ = run_and_check(K, V, S, L, 0.3, variant=variant,
+                               launch=hint(lagkv.PATH_FUSED, 4, select=lagkv.SELECT_GROUP))
+        k = out.plan.k
+        assert torch.equal(out.idx[0, 0, S:S + k].cpu(), torch.arange(S, S + k, dtype=torch.int32))
+
+
+RESIDENT_SHAPES = [
+    # B, H, n_chunks, rem, D, dtype, L, r, segments
+    (2, 2, 6, 37, 128, torch.bfloat16, 512, 0.25, 1),
+    (1, 3, 9, 0, 128, torch.bfloat16, 512, 0.125, 2),
+    (2, 1, 11, 5, 128, torch.bfloat16, 256, 0.125, 1),      # 2 chunks per batch, odd chunk count
+    (1, 2, 14, 100, 128, torch.bfloat16, 128, 0.25, 3),     # 4 chunks per batch, ragged segments
+    (1, 2, 3, 1, 128, torch.bfloat16, 128, 0.5, 1),         # fewer chunks than one batch
+    (1, 2, 7, 9, 64, torch.float32, 256, 0.167, 2),
+    (1, 2, 6, 9, 128, torch.float16, 128, 0.33, 1),
+    (1, 1, 2, 0, 128, torch.bfloat16, 512, 0.5, 1),         # one scored chunk
+]
+
+
+@pytest.mark.parametrize("shape", RESIDENT_SHAPES, ids=lambda s: f"B{s[0]}H{s[1]}n{s[2]}m{s[3]}D{s[4]}{str(s[5]).split('.')[-1]}L{s[6]}r{s[7]}seg{s[8]}")
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL])
+def test_register_resident_kernel_against_oracle(shape, variant):
+    """The one-shot kernel that keeps a batch of rows in registers (every row read once)."""
+    B, H, n, m, D, dtype, L, r, nseg = shape
+    S = 16
+    say("resident kernel", shape, "variant", variant)
+    K, V = gen(B, H, S + n * L + m, D, dtype, seed=n * 31 + L)
+    K[0, 0, S + 3] = K[0, 0, S + 1]; V[0, 0, S + 3] = V[0, 0, S + 1]          # an exact tie
+    out, rep = run_and_check(K, V, S, L, r, variant=variant, launch=hint(lagkv.PATH_RESIDENT, segments=nseg))
+    assert rep.chunks == B * H * (n - 1)
+    sc = lagkv.score(K, V, S, L, r, variant=variant, launch=hint(lagkv.PATH_RESIDENT, segments=nseg))
+    torch.cuda.synchronize()
+    assert torch.equal(sc, out.scores)
+
+
+def test_register_resident_kernel_refuses_other_shapes():
+    K, V = gen(1, 1, 16 + 3 * 100, 128, torch.bfloat16, seed=1)
+    for kw in (dict(L=100), dict(L=128, variant=lagkv.SCORE_L2)):
+        with pytest.raises(lagkv.LagKVError) as e:
+            lagkv.compress(K, V, 16, kw.get("L"), 0.25, variant=kw.get("variant", lagkv.SCORE_LAG),
+                           launch=hint(lagkv.PATH_RESIDENT))
+        assert e.value.status == lagkv.ESHAPE
 
 
 def test_strided_input_views():
@@ -143,8 +223,7 @@ def test_noop_below_two_lags_and_identity_at_r1():
     assert lagkv.score(K, V, 16, 128, 0.25).numel() == 0
     K, V = gen(1, 2, 16 + 4 * 32 + 5, 128, torch.bfloat16, seed=4)
     for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
-        lagkv.tune(lagkv.TUNE_PATH, path)
-        out = lagkv.compress(K, V, 16, 32, 1.0)
+        out = lagkv.compress(K, V, 16, 32, 1.0, launch=hint(path))
         torch.cuda.synchronize()
         assert torch.equal(out.K, K) and torch.equal(out.V, V)
 
@@ -156,8 +235,7 @@ def test_degenerate_channel_and_duplicate_tokens(path):
     K[:, :, 8 + 64:8 + 128, 5] = 1.25          # constant channel in the reference of chunk 0
     V[:, :, :, 17] = -3.0                      # constant in every reference
     K[0, 0, 8 + 10] = K[0, 0, 8 + 3]; V[0, 0, 8 + 10] = V[0, 0, 8 + 3]   # exact duplicates -> exact tie
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    out, rep = run_and_check(K, V, 8, 64, 0.5)
+    out, rep = run_and_check(K, V, 8, 64, 0.5, launch=hint(path))
     sc = out.scores[0, 0].cpu()
     assert torch.isfinite(out.scores).all()
     assert sc[3] == sc[10]
@@ -170,19 +248,21 @@ def test_degenerate_channel_and_duplicate_tokens(path):
                                          (torch.float32, 128, 24, 0.5)])
 def test_scoring_variants(variant, dtype, D, L, r, path):
     say("variant", variant, dtype, D, L, "path", path)
-    if path == lagkv.PATH_FUSED and D == 48:
-        pytest.skip("192-byte rows are served by the three-kernel path only")
     K, V = gen(2, 2, 16 + 5 * L + 3, D, dtype, seed=31 + variant)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    run_and_check(K, V, 16, L, r, variant=variant)
+    if path == lagkv.PATH_FUSED and D == 48:
+        # 192-byte rows are served by the three-kernel path only; asking for the fused one is an error
+        with pytest.raises(lagkv.LagKVError) as e:
+            lagkv.compress(K, V, 16, L, r, variant=variant, launch=hint(path))
+        assert e.value.status == lagkv.ESHAPE
+        return
+    run_and_check(K, V, 16, L, r, variant=variant, launch=hint(path))
 
 
 @pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
 def test_l2_scores_need_no_values(path):
     """Eq. 16 reads K only: lagkv_score accepts V = NULL for it."""
     K, _ = gen(1, 2, 8 + 4 * 128, 128, torch.bfloat16, seed=77)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    sc = lagkv.score(K, None, 8, 128, 0.25, variant=lagkv.SCORE_L2)
+    sc = lagkv.score(K, None, 8, 128, 0.25, variant=lagkv.SCORE_L2, launch=hint(path))
     torch.cuda.synchronize()
     want = -torch.linalg.vector_norm(K[:, :, 8:8 + 3 * 128].double(), dim=-1)
     assert torch.allclose(sc.double(), want, rtol=1e-5, atol=0)
@@ -191,8 +271,7 @@ def test_l2_scores_need_no_values(path):
 def test_ddof_zero():
     K, V = gen(1, 2, 16 + 3 * 64, 128, torch.bfloat16, seed=41)
     for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
-        lagkv.tune(lagkv.TUNE_PATH, path)
-        run_and_check(K, V, 16, 64, 0.25, ddof=0)
+        run_and_check(K, V, 16, 64, 0.25, ddof=0, launch=hint(path))
 
 
 # ------------------------------------------------------- stage-by-stage entry points
@@ -200,8 +279,7 @@ def test_score_entry_point_matches_oracle():
     say("lagkv_score")
     K, V = gen(2, 2, 16 + 4 * 128 + 9, 128, torch.bfloat16, seed=51)
     for path in (lagkv.PATH_FUSED, lagkv.PATH_STAGED):
-        lagkv.tune(lagkv.TUNE_PATH, path)
-        sc = lagkv.score(K, V, 16, 128, 0.25)
+        sc = lagkv.score(K, V, 16, 128, 0.25, launch=hint(path))
         torch.cuda.synchronize()
         for b in range(2):
             for h in range(2):
@@ -254,8 +332,7 @@ def test_append_from_empty_equals_one_shot(path, steps):
     S, L, r, D = 6, 32, 0.25, 128
     T = sum(steps)
     Kh, Vh = gen(1, 2, T, D, torch.bfloat16, seed=61)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    cache = lagkv.Cache(1, 2, D, T + 8, S, L, r)
+    cache = lagkv.Cache(1, 2, D, T + 8, S, L, r, launch=hint(path))
     t = 0
     for n in steps:
         cache.append_and_compress(Kh[:, :, t:t + n], Vh[:, :, t:t + n])
@@ -267,17 +344,24 @@ def test_append_from_empty_equals_one_shot(path, steps):
 
 @pytest.mark.parametrize("path", [lagkv.PATH_FUSED, lagkv.PATH_STAGED])
 @pytest.mark.parametrize("dtype,D,variant", [(torch.bfloat16, 128, lagkv.SCORE_LAG), (torch.float32, 64, lagkv.SCORE_LAG),
-                                             (torch.bfloat16, 128, lagkv.SCORE_LOCAL), (torch.float32, 40, lagkv.SCORE_L2)])
+                                             (torch.bfloat16, 128, lagkv.SCORE_LOCAL), (torch.float32, 40, lagkv.SCORE_L2),
+                                             (torch.bfloat16, 128, lagkv.SCORE_L2), (torch.float16, 64, lagkv.SCORE_L2)])
 def test_append_after_one_shot_equals_one_shot_on_history(path, dtype, D, variant):
-    if path == lagkv.PATH_FUSED and (D == 40 or variant == lagkv.SCORE_L2):
-        pytest.skip("shape/variant served by the three-kernel path only")
     say("append after compress", dtype, D, variant, "path", path)
     S, L, r = 16, 64, 0.25
     T0, rounds = 16 + 6 * 64 + 20, 5
     Kh, Vh = gen(2, 2, T0 + rounds * L, D, dtype, seed=71)
-    lagkv.tune(lagkv.TUNE_PATH, path)
-    comp = lagkv.compress(Kh[:, :, :T0].contiguous(), Vh[:, :, :T0].contiguous(), S, L, r, variant=variant)
-    cache = lagkv.Cache.from_compressed(comp, T0, comp.plan.T_out + 3 * L, S, L, r, variant=variant)
+    if path == lagkv.PATH_FUSED and D == 40:
+        # 160-byte rows are served by the three-kernel path only; asking for the fused one is an error
+        cache = lagkv.Cache(2, 2, D, T0, S, L, r, dtype=dtype, variant=variant, launch=hint(path))
+        with pytest.raises(lagkv.LagKVError) as e:
+            cache.append_and_compress(Kh[:, :, :T0], Vh[:, :, :T0])
+        assert e.value.status == lagkv.ESHAPE and cache.length == 0
+        return
+    comp = lagkv.compress(Kh[:, :, :T0].contiguous(), Vh[:, :, :T0].contiguous(), S, L, r, variant=variant,
+                          launch=hint(path))
+    cache = lagkv.Cache.from_compressed(comp, T0, comp.plan.T_out + 3 * L, S, L, r, variant=variant,
+                                        launch=hint(path))
     for i in range(rounds):
         a = T0 + i * L
         cache.append_and_compress(Kh[:, :, a:a + L], Vh[:, :, a:a + L])     # strided views of the history
@@ -286,36 +370,38 @@ def test_append_after_one_shot_equals_one_shot_on_history(path, dtype, D, varian
     oracle_history_check(cache, Kh, Vh, S, L, r, VARIANT_NAME[variant])
 
 
+@pytest.mark.parametrize("variant,select", [(lagkv.SCORE_LAG, lagkv.SELECT_AUTO), (lagkv.SCORE_L2, lagkv.SELECT_AUTO),
+                                            (lagkv.SCORE_LAG, lagkv.SELECT_GROUP), (lagkv.SCORE_L2, lagkv.SELECT_GROUP)])
 @pytest.mark.parametrize("L,D,dtype,r", [(32, 128, torch.bfloat16, 0.25), (24, 64, torch.float32, 0.5),
                                          (128, 128, torch.bfloat16, 0.25), (70, 32, torch.bfloat16, 0.1),
                                          (16, 256, torch.bfloat16, 0.9), (50, 128, torch.float32, 0.33)])
-def test_single_round_decode_step_with_the_boundary_anywhere(L, D, dtype, r):
+def test_single_round_decode_step_with_the_boundary_anywhere(L, D, dtype, r, variant, select):
     """The steady decode step (exactly one chunk completes) with the border between cached
-    and new rows inside the chunk, inside the reference, at their ends, and in the rest."""
+    and new rows inside the chunk, inside the reference, at their ends, and in the rest; Eq. 7-11
+    and Eq. 16 scoring, selection by one wavefront and by the whole workgroup."""
     S = 5
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
     cases = [(0, 2 * L), (1, 3 * L - 2), (L - 1, L + 1), (L, L), (L + 1, L - 1), (L + L // 2, L // 2 + 3),
              (2 * L - 1, 1), (2 * L - 1, L), (L + 3, 2 * L - 4)]
     for n_tail, n_new in cases:
         say("decode step", L, D, dtype, "tail", n_tail, "new", n_new)
         T = S + n_tail + n_new
         Kh, Vh = gen(2, 3, T, D, dtype, seed=L * 7 + n_tail)
-        cache = lagkv.Cache(2, 3, D, T + 4, S, L, r, dtype=dtype)
+        cache = lagkv.Cache(2, 3, D, T + 4, S, L, r, dtype=dtype, variant=variant,
+                            launch=hint(lagkv.PATH_FUSED, select=select))
         cache.append_and_compress(Kh[:, :, :S + n_tail], Vh[:, :, :S + n_tail])
         assert cache.n_static == S and cache.n_tail == n_tail
         cache.append_and_compress(Kh[:, :, S + n_tail:], Vh[:, :, S + n_tail:])
         torch.cuda.synchronize()
         assert cache.n_tail == n_tail + n_new - L
-        oracle_history_check(cache, Kh, Vh, S, L, r)
+        oracle_history_check(cache, Kh, Vh, S, L, r, VARIANT_NAME[variant])
 
 
 def test_single_round_decode_step_repeats_and_without_positions():
     S, L, r, D = 16, 128, 0.25, 128
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_FUSED)
     T = S + 2 * L + 112 + 5 * L
     Kh, Vh = gen(1, 4, T, D, torch.bfloat16, seed=99)
-    with_pos = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=True)
-    without = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=False)
+    with_pos = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=True, launch=hint(lagkv.PATH_FUSED))
+    without = lagkv.Cache(1, 4, D, T, S, L, r, track_positions=False, launch=hint(lagkv.PATH_FUSED))
     t = 0
     for n in [S + L + 112] + [L] * 6:
         say("decode steps", t, n)
@@ -335,7 +421,6 @@ def test_prefill_chunk_by_chunk_equals_one_shot(dtype):
     S, L, r, D = 16, 64, 0.25, 128
     T = S + 2 * L + 7 * L + 13
     Kh, Vh = gen(2, 2, T, D, dtype, seed=123)
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
     cache = lagkv.Cache(2, 2, D, T, S, L, r, dtype=dtype)
     calls = cache.prefill_chunked(Kh, Vh)
     torch.cuda.synchronize()
@@ -428,7 +513,6 @@ def test_compress_can_be_captured_in_a_graph_and_replayed(L):
     reproduce the eager result."""
     S, r = 16, 0.25
     K, V = gen(2, 4, S + 9 * L + 17, 128, torch.bfloat16, seed=404)
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
     eager = lagkv.compress(K, V, S, L, r)
     torch.cuda.synchronize()
     Ko, Vo = torch.zeros_like(eager.K), torch.zeros_like(eager.V)
@@ -467,7 +551,6 @@ def test_config5_decode_full_batch_sampled_streams():
     cfg = synth.CONFIGS["cfg5_decode_b32"]
     rounds = 16
     say("config 5 full batch", cfg.streams, "streams")
-    lagkv.tune(lagkv.TUNE_PATH, lagkv.PATH_AUTO)
     pl = lagkv.plan(lagkv.make_params(cfg.layers * cfg.B, cfg.H, cfg.D, cfg.S, cfg.L, cfg.r), cfg.T)
     assert pl.T_out == 8384
     cap = pl.T_out + rounds * pl.k + cfg.L
@@ -489,8 +572,7 @@ def test_config5_decode_full_batch_sampled_streams():
                 hist[s][0].append(Kl[bb - l * cfg.B, h].cpu())
                 hist[s][1].append(Vl[bb - l * cfg.B, h].cpu())
     del Kl, Vl, comp
-    n_static = cfg.S + pl.k * pl.n_scored
-    cache.c.n_static, cache.c.n_tail, cache.c.n_seen = n_static, pl.T_out - n_static, cfg.T
+    cache.mark_compressed(cfg.T)
     for i in range(rounds):
         Kn, Vn = synth.make_new_tokens(cfg, cfg.L, i, device=DEV)
         cache.append_and_compress(Kn, Vn)
