@@ -168,6 +168,26 @@ typedef struct {
 } lagkv_cache;
 
 /*
+ * lagkv_compress for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as lagkv_compress without ws / ws_bytes: when the three-kernel path
+ * is taken, its scores and kept positions are staged in a fixed device array inside the
+ * library (LAGKV_STATIC_SCRATCH_BYTES per GPU, held from the first call on that GPU until
+ * the process ends) instead.  The call allocates and frees nothing.
+ *   - LAGKV_EWORKSPACE when the pass would need more than LAGKV_STATIC_SCRATCH_BYTES
+ *     (use lagkv_compress with a workspace then); nothing is enqueued.
+ *   - The device that is current when the call is made must be the stream's device.
+ *   - All calls on one GPU share that GPU's array: two calls that may run at the same time
+ *     (different streams, different threads) race on it and must be serialised by the
+ *     caller.  Nothing in the array has to be cleared between calls: every word a kernel
+ *     reads is written earlier in the same call.
+ */
+#define LAGKV_STATIC_SCRATCH_BYTES (16u << 20)
+int lagkv_compress_static(const lagkv_params* p, const void* K, const void* V, int64_t T,
+                          void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                          void* hip_stream);
+
+/*
  * Host only: set the counters of `cache` to the state of a cache that holds the output of
  * lagkv_compress on T rows (Eq. 12: n_static = S + k*n_scored, n_tail = L + rem,
  * n_seen = T; when T - S < 2L nothing was compressed: n_static = min(T, S),

@@ -12,7 +12,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblagkv.so")
-SOURCES = ["lagkv_api.hip", "split_pass.hip", "hold_pass.hip", "append_pass.hip", "staged_pass.hip"]
+SOURCES = ["lagkv_api.hip", "split_pass.hip", "hold_pass.hip", "append_pass.hip", "staged_pass.hip",
+           "static_scratch.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

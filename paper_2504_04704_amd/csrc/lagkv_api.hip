@@ -357,6 +357,19 @@ int lagkv_compress(const lagkv_params* p, const void* K, const void* V, int64_t 
 
 }  // extern "C"
 
+// Workspace one lagkv_compress call needs (0: the fused kernels serve it, or the parameters
+// are invalid and the call itself will say so).
+size_t lagkv::compress_workspace_need(const lagkv_params* p, int64_t T) {
+  Norm n;
+  if (validate(p, &n) != LAGKV_OK || T < 1 || T > kMaxRows) return 0;
+  int64_t sb, sh, st;
+  if (strides_of(p, n, T, &sb, &sh, &st) != LAGKV_OK) return 0;
+  if (n.hint.path != LAGKV_PATH_STAGED && shape_fused(n, sb, sh, st) && fused_fits(n)) return 0;
+  lagkv_plan_t pl;
+  plan_of(n, T, n.S, &pl);
+  return pl.n_scored > 0 ? staged_ws(n, pl.n_scored, true).total : 0;
+}
+
 // The whole pass with the workspace given by the caller (lagkv_compress) or taken from the
 // library's static scratch (lagkv_compress_static).
 int lagkv::compress_with_workspace(const lagkv_params* p, const void* K, const void* V, int64_t T,

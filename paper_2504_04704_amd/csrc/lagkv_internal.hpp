@@ -9,7 +9,9 @@
 
 namespace lagkv {
 
-// lagkv_compress with an explicit workspace (defined in lagkv_api.hip).
+// Workspace bytes of one lagkv_compress call, and lagkv_compress with an explicit workspace
+// (both defined in lagkv_api.hip).
+size_t compress_workspace_need(const lagkv_params* p, int64_t T);
 int compress_with_workspace(const lagkv_params* p, const void* K, const void* V, int64_t T,
                             void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
                             size_t ws_bytes, void* hip_stream);

@@ -26,7 +26,8 @@ ORDER_LINEAR, ORDER_EVEN_ODD, ORDER_XCD, ORDER_BITREV = 0, 1, 2, 3
 SELECT_AUTO, SELECT_WAVE, SELECT_GROUP = 0, 1, 2
 
 EXPORTS = ("lagkv_plan", "lagkv_keep_for_compression", "lagkv_workspace_bytes", "lagkv_score",
-           "lagkv_select", "lagkv_compress", "lagkv_cache_after_compress", "lagkv_prefill_rows",
+           "lagkv_select", "lagkv_compress", "lagkv_compress_static", "lagkv_cache_after_compress",
+           "lagkv_prefill_rows",
            "lagkv_append_and_compress", "lagkv_launch_hint", "lagkv_launch_hint_ex", "lagkv_strerror",
            "lagkv_version")
 
@@ -87,6 +88,8 @@ def load():
     lib.lagkv_append_and_compress.argtypes = [C.POINTER(Params), C.POINTER(CacheT), vp, vp, i64, vp,
                                               sz, vp]
     lib.lagkv_append_and_compress.restype = C.c_int
+    lib.lagkv_compress_static.argtypes = [C.POINTER(Params), vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.lagkv_compress_static.restype = C.c_int
     lib.lagkv_cache_after_compress.argtypes = [C.POINTER(Params), i64, C.POINTER(CacheT)]
     lib.lagkv_cache_after_compress.restype = C.c_int
     lib.lagkv_prefill_rows.argtypes = [C.POINTER(Params), C.POINTER(CacheT), i64]
@@ -257,6 +260,30 @@ def compress(K: torch.Tensor, V: torch.Tensor, S: int, L: int, r: float, variant
                                  0 if ws is None else ws.numel(), _stream_ptr(K.device)),
            "lagkv_compress")
     return Compressed(Ko, Vo, idx_out, scores_out, pl)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def compress_static(K: torch.Tensor, V: torch.Tensor, S: int, L: int, r: float, out: Tuple[torch.Tensor, torch.Tensor],
+                    idx_out: Optional[torch.Tensor] = None, scores_out: Optional[torch.Tensor] = None,
+                    variant=SCORE_LAG, std_ddof: int = 1, launch: int = 0) -> PlanT:
+    """lagkv_compress_static: the whole pass into caller-provided buffers with no workspace and no
+    allocation anywhere (the three-kernel path stages in the library's static device array)."""
+    if not K.is_cuda:
+        raise RuntimeError("lagkv.compress_static needs device tensors; there is no CPU path")
+    _same_layout(K, V)
+    p = params_for(K, S, L, r, variant, std_ddof, launch)
+    B, H, T, D = K.shape
+    pl = plan(p, T)
+    Ko, Vo = out
+    if tuple(Ko.shape) != (B, H, pl.T_out, D) or not Ko.is_contiguous() or not Vo.is_contiguous() \
+            or Vo.shape != Ko.shape or Ko.dtype != K.dtype or Vo.dtype != K.dtype:
+        raise ValueError("output buffers must be dense [B,H,T_out,D] of the input dtype")
+    _check(load().lagkv_compress_static(C.byref(p), K.data_ptr(), V.data_ptr(), T, Ko.data_ptr(),
+                                        Vo.data_ptr(), _ptr(idx_out), _ptr(scores_out),
+                                        _stream_ptr(K.device)), "lagkv_compress_static")
+    return pl
 
 
 class Cache:
