@@ -3,21 +3,32 @@
 //
 // A workgroup of eight wavefronts (four on K rows, four on V rows) walks a segment of one
 // stream backwards, one BATCH of 512 rows at a time (1, 2 or 4 chunks).  The 32 row
-// slices a lane loads for a batch stay in 128 of its registers until the selection is
+// slices a lane handles in a batch stay in 128 of its registers until the selection is
 // known; the kept rows are then stored from those registers, so the compaction reads
 // nothing.  (A chunk of K and V is up to 256 KiB, more than the LDS of a CU but half of
 // its register file: one workgroup per CU, two wavefronts per SIMD, 256 registers each.)
+//
+// With a single workgroup on a CU nothing else hides its selection, so the memory stream
+// is kept going from inside:
+//   * rows arrive through a per-wavefront LDS ring filled by asynchronous global->LDS loads
+//     that run a fixed number of steps AHEAD of the arithmetic, across batch borders: while
+//     a batch is folded and selected, the first steps of the next batch are in flight;
+//   * the stores of a batch's kept rows are deferred into the next batch's sweep: slice s
+//     of the old batch is stored right before slice s of the new batch replaces it.
 // Per batch:
-//   1. issue all 32 loads of the lane (32 KiB in flight per wavefront);
-//   2. per chunk, fold the rows into per-channel min/max (Eq. 7-8) as they arrive, reduce
-//      over the wavefront and park the partial result in LDS;            -- barrier --
-//   3. per chunk, take the reference statistics (the next chunk's, Eq. 7-8, or the
-//      chunk's own, Eq. 14-15) and compute every token's channel variance from the
-//      registers (Eq. 9-10).  A batch of ONE chunk whose reference is the previous
-//      batch's chunk does 2 and 3 in a single sweep;                     -- barrier --
-//   4. chunk softmax, K+V sum and top-k (Eq. 10-11): all wavefronts together for a
-//      512-row chunk, one wavefront per chunk otherwise;                 -- barrier --
-//   5. store the kept rows from the registers, and their original positions.
+//   1. sweep: per slice, store the previous batch's slice if kept, take the new slice from
+//      the ring, fold it into the per-channel min/max of its chunk (Eq. 7-8); park the
+//      wavefront's partial result in LDS.  A batch of ONE chunk whose reference is the
+//      previous batch's chunk computes the token variances (Eq. 9-10) in the same sweep;
+//                                                                        -- barrier --
+//   2. otherwise, per chunk, take the reference statistics (the next chunk's, Eq. 7-8, or
+//      the chunk's own, Eq. 14-15) and compute the variances from the registers;
+//                                                                        -- barrier --
+//   3. chunk softmax, K+V sum and top-k (Eq. 10-11): all wavefronts together for a
+//      512-row chunk, one wavefront per chunk otherwise; original positions are written.
+//                                                                        -- barrier --
+// All vector-memory traffic of the loop is issued from assembly with explicit counter
+// waits (the compiler sees none of it and therefore never drains it at a barrier).
 #include "lagkv_internal.hpp"
 #include "lds_dma.hpp"
 #include "row_ops.hpp"
@@ -29,22 +40,11 @@ namespace lagkv {
 constexpr int kHoldSteps = 32;   // row slices a lane keeps per batch
 constexpr int kHoldWaves = 8;
 
-// Row loads go through a raw buffer descriptor: the batch's first row is the (scalar) base,
-// the lane's place in a step one 32-bit vector offset shared by all 32 loads, the step a
-// scalar offset - no per-load 64-bit vector address, which is what lets 128 registers of
-// row data and the arithmetic state fit a 256-register wavefront.
-typedef uint32_t buf_u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_buffer(const char* base) {
-  // untyped 32-bit data format, no stride, range = the whole 32-bit offset space
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, 0xffffffff, 0x00020000);
-}
-__device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t step_off) {
-  const buf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, step_off, 0);
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
+// Ring slots (1 KiB steps) per wavefront; divides kHoldSteps so that a step's slot is static.
+__host__ __device__ constexpr int hold_ring(int C) { return C == 1 ? 16 : 8; }
 
 struct HoldLds {
-  int off_vK, off_vV, off_slot, off_list, off_sel, off_stat, total;  // bytes
+  int off_vK, off_vV, off_slot, off_list, off_sel, off_stat, off_ring, total;  // bytes
 };
 // rows: rows per batch; C: chunks per batch
 __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C) {
@@ -56,14 +56,42 @@ __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C) {
   l.off_list = 3 * rows * 4;                 // uint32 [C][kp]
   l.off_sel = l.off_list + C * kp * 4;
   l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;   // float [2][C][wave][mn|mx][D]
-  l.total = l.off_stat + 2 * C * kHoldWaves * 2 * D * 4;
+  l.off_ring = (l.off_stat + 2 * C * kHoldWaves * 2 * D * 4 + 1023) & ~1023;
+  l.total = l.off_ring + kHoldWaves * hold_ring(C) * 1024;
   return l;
 }
 
-// NSC: steps (of R = 4 * 64/LPR rows) per chunk: L = NSC * R; C = 32 / NSC chunks per batch.
+// One-off 16-byte row loads before the loop, through a raw buffer descriptor (untyped
+// 32-bit data format, no stride, range = the whole 32-bit offset space): scalar base, one
+// 32-bit lane offset, scalar step offset.
+typedef uint32_t buf_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 buf_ld16(const char* base, uint32_t lane_off, uint32_t step_off) {
+  const __amdgpu_buffer_rsrc_t r =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, 0xffffffff, 0x00020000);
+  const buf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, step_off, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Workgroup barrier for LDS traffic only: waits for this wavefront's LDS operations, not for
+// its vector-memory operations (a __syncthreads() carries a fence that may wait for those).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// f(integral_constant<int, I>) for I = BEGIN, BEGIN + STEP, ... < END
+template <int BEGIN, int END, int STEP, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>{});
+    static_for<BEGIN + STEP, END, STEP>(f);
+  }
+}
+
+// NSC: steps (of R = 16 rows) per chunk: L = NSC * R; C = 32 / NSC chunks per batch.
 // LOCAL: Eq. 14-15 (a chunk is its own reference) instead of Eq. 7-8.
-template <typename ET, int LPR, int NSC, bool LOCAL>
+template <typename ET, int NSC, bool LOCAL>
 __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
+  constexpr int LPR = 16;
   constexpr int VEC = ET::VEC;
   constexpr int RPW = kWave / LPR;
   constexpr int G = kHoldWaves / 2;
@@ -71,6 +99,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   constexpr int C = kHoldSteps / NSC;
   constexpr int L = NSC * R;
   constexpr int E = (L + kWave - 1) / kWave;
+  constexpr int NR = hold_ring(C);
   // one chunk per batch whose reference is the previous batch's chunk: a single sweep
   constexpr bool single = C == 1 && !LOCAL;
   constexpr bool local = LOCAL;
@@ -129,7 +158,11 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   const int64_t p0 = (int64_t)seg * a.n_s / a.nseg;
   const int64_t p1 = (int64_t)(seg + 1) * a.n_s / a.nseg;
   const uint32_t lane_off = (uint32_t)(row0 * a.st) + (uint32_t)cl * 16u;
-  const uint32_t step_bytes = (uint32_t)(R * a.st);
+  const int64_t step_bytes = (int64_t)R * a.st;
+  // this wavefront's ring (wave-uniform LDS byte address) and the lane's 16 bytes in a slot
+  const uint32_t ring_base =
+      __builtin_amdgcn_readfirstlane(lds_offset(lds + lay.off_ring) + (uint32_t)wave * (NR * 1024u));
+  const uint32_t ring_lane = ring_base + (uint32_t)lane * 16u;
 
   uint4 hold[kHoldSteps];
   TStats<VEC> acc;
@@ -176,9 +209,9 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
 
   if constexpr (!local) {
     // statistics of the chunk after the segment: the first reference
-    const __amdgpu_buffer_rsrc_t rows = row_buffer(tin + (S + p1 * L) * a.st);
+    const char* first = tin + (S + p1 * L) * a.st;
 #pragma unroll
-    for (int j = 0; j < NSC; ++j) hold[j] = buf_ld16(rows, lane_off, (uint32_t)j * step_bytes);
+    for (int j = 0; j < NSC; ++j) hold[j] = buf_ld16(first, lane_off, (uint32_t)(j * step_bytes));
     acc.reset();
 #pragma unroll
     for (int j = 0; j < NSC; ++j) {
@@ -193,60 +226,88 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     q = 1;     // parked as chunk 0 of the batch "before" the first one
     park(0);
     q = 0;
-    __syncthreads();
   }
+  // Everything the compiler knows to be in flight (the copies and loads above) is drained
+  // here, once; inside the loop it sees no vector-memory operation at all.
+  __syncthreads();
+
+  int64_t pb = p1 - C > p0 ? p1 - C : p0;
+  int nsb = (int)(p1 - pb) * NSC;                       // steps of the current batch
+  const char* rows = tin + (S + pb * L) * a.st;         // its first row (of this tensor)
+#pragma unroll
+  for (int s = 0; s < NR; ++s)                          // nsb >= NSC >= NR
+    dma_rows16(lane_off, rows + (int64_t)s * step_bytes, ring_base + (uint32_t)s * 1024u);
+
+  int64_t prev_pb = 0;
+  int prev_nsb = 0;                                     // steps of the previous batch still to be stored
+
+  // kept slices s, s+1 of the previous batch -> output (chunk c of that batch)
+  auto store_prev = [&](int s, int c) __attribute__((always_inline)) {
+    char* dst = tout + (S + (prev_pb + c) * k) * rowbytes;  // wave-uniform
+    const int sl0 = slotmap[s * R + row0], sl1 = slotmap[(s + 1) * R + row0];
+    if (sl0 >= 0) st16_out_at(dst, (uint32_t)sl0 * (uint32_t)rowbytes + (uint32_t)coff, hold[s]);
+    if (sl1 >= 0) st16_out_at(dst, (uint32_t)sl1 * (uint32_t)rowbytes + (uint32_t)coff, hold[s + 1]);
+  };
 
   for (int64_t pe = p1; pe > p0;) {
-    const int64_t pb = pe - C > p0 ? pe - C : p0;
-    const int cb = (int)(pe - pb);  // chunks of this batch (the last batch of a segment may be short)
-    const __amdgpu_buffer_rsrc_t rows = row_buffer(tin + (S + pb * L) * a.st);
+    const int cb = nsb / NSC;  // chunks of this batch (the last batch of a segment may be short)
+    const int64_t next_pb = pb - C > p0 ? pb - C : p0;
+    const int next_nsb = (int)(pb - next_pb) * NSC;     // 0: this is the last batch of the segment
+    const char* next_rows = tin + (S + next_pb * L) * a.st;
     if constexpr (single) folded(q ^ 1, 0, ref);
 
-    // 1. all loads of the batch
+    // 1. sweep (unrolled over the pairs of steps; s is a compile-time constant)
+    static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
+      constexpr int s = decltype(step_tag)::value;
+      constexpr int c = s / NSC;
+      if constexpr (s % NSC == 0) acc.reset();
+      if (gather && s < prev_nsb) store_prev(s, c);
+      if (s < nsb) {
+        // Steps s and s+1 have landed once at most NR-2 younger loads are pending (the stores
+        // issued in between only make this wait stricter: operations complete in order); near
+        // the end of the segment fewer loads were issued, so everything is waited for.
+        u32x4 qa, qb;
+        const uint32_t la = ring_lane + (uint32_t)(s % NR) * 1024u;
+        const uint32_t lb = ring_lane + (uint32_t)((s + 1) % NR) * 1024u;
+        if (s + NR <= nsb + next_nsb) lds_read_pair_after<NR - 2>(qa, qb, la, lb);
+        else lds_read_pair_after<0>(qa, qb, la, lb);
+        // the two slots are free again: the loads NR steps ahead, into the next batch if need be
+        constexpr int t = s + NR;
+        if (t < nsb) {
+          dma_rows16(lane_off, rows + (int64_t)t * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
+          dma_rows16(lane_off, rows + (int64_t)(t + 1) * step_bytes, ring_base + (uint32_t)((t + 1) % NR) * 1024u);
+        } else if (t - nsb < next_nsb) {
+          dma_rows16(lane_off, next_rows + (int64_t)(t - nsb) * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
+          dma_rows16(lane_off, next_rows + (int64_t)(t + 1 - nsb) * step_bytes,
+                     ring_base + (uint32_t)((t + 1) % NR) * 1024u);
+        }
+        hold[s] = make_uint4(qa.x, qa.y, qa.z, qa.w);
+        hold[s + 1] = make_uint4(qb.x, qb.y, qb.z, qb.w);
+        float x0[VEC], x1[VEC];
+        unpack<ET>(hold[s], x0);
+        unpack<ET>(hold[s + 1], x1);
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-      if (c < cb) {
-#pragma unroll
-        for (int j = 0; j < NSC; ++j) {
-          const int s = c * NSC + j;
-          hold[s] = buf_ld16(rows, lane_off, (uint32_t)s * step_bytes);
+        for (int i = 0; i < VEC; ++i) {
+          acc.mn[i] = fminf(fminf(acc.mn[i], x0[i]), x1[i]);
+          acc.mx[i] = fmaxf(fmaxf(acc.mx[i], x0[i]), x1[i]);
+        }
+        pin(acc);
+        if constexpr (single) {
+          const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          if (cl == 0) {
+            myvar[s * R + row0] = v0;
+            myvar[(s + 1) * R + row0] = v1;
+          }
         }
       }
-    }
-    __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first row is waited for
-    // 2. per-channel min/max of every chunk (and, for a single chunk with a known
-    // reference, the variances in the same sweep)
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-      if (c < cb) {
-        acc.reset();
-#pragma unroll
-        for (int j = 0; j < NSC; j += 2) {
-          const int s = c * NSC + j;
-          float x0[VEC], x1[VEC];
-          unpack<ET>(hold[s], x0);
-          unpack<ET>(hold[s + 1], x1);
-#pragma unroll
-          for (int i = 0; i < VEC; ++i) {
-            acc.mn[i] = fminf(fminf(acc.mn[i], x0[i]), x1[i]);
-            acc.mx[i] = fmaxf(fmaxf(acc.mx[i], x0[i]), x1[i]);
-          }
-          pin(acc);
-          if constexpr (single) {
-            const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-            const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-            if (cl == 0) {
-              myvar[s * R + row0] = v0;
-              myvar[(s + 1) * R + row0] = v1;
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);  // keep the pairs in order: interleaving them costs registers
-        }
-        park(c);
+      __builtin_amdgcn_sched_barrier(0);  // keep the pairs in order: interleaving them costs registers
+      if constexpr ((s + 2) % NSC == 0) {
+        if (c < cb) park(c);
       }
-    }
-    __syncthreads();
-    // 3. variances of every chunk against its reference
+    });
+    lds_barrier();
+    // 2. variances of every chunk against its reference
     if constexpr (!single) {
 #pragma unroll
       for (int c = 0; c < C; ++c) {
@@ -258,12 +319,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
           for (int j = 0; j < NSC; j += 2) {
             const int s = c * NSC + j;
             float x0[VEC], x1[VEC];
-            // (opaque to the compiler, so that it unpacks again here instead of keeping the
-            // first sweep's unpacked rows alive in registers)
-            asm volatile("" : "+v"(hold[s].x), "+v"(hold[s].y), "+v"(hold[s].z), "+v"(hold[s].w));
-            asm volatile("" : "+v"(hold[s + 1].x), "+v"(hold[s + 1].y), "+v"(hold[s + 1].z), "+v"(hold[s + 1].w));
-            unpack<ET>(hold[s], x0);
-            unpack<ET>(hold[s + 1], x1);
+            // (copies made opaque to the compiler, so that it unpacks again here instead of
+            // keeping the first sweep's unpacked rows alive in registers)
+            uint4 t0 = hold[s], t1 = hold[s + 1];
+            asm volatile("" : "+v"(t0.x), "+v"(t0.y), "+v"(t0.z), "+v"(t0.w));
+            asm volatile("" : "+v"(t1.x), "+v"(t1.y), "+v"(t1.z), "+v"(t1.w));
+            unpack<ET>(t0, x0);
+            unpack<ET>(t1, x1);
             const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
             const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
             if (cl == 0) {
@@ -274,9 +336,9 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
           }
         }
       }
+      lds_barrier();
     }
-    if constexpr (!single) __syncthreads();
-    // 4. scores and selection
+    // 3. scores and selection
     if constexpr (C == 1) {
       group_score_select(vK, vV, L, k, gather, sout ? sout + pb * L : nullptr, selbuf, list, slotmap, tid,
                          nthreads);
@@ -285,32 +347,27 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         wave_score_select<E>(vK + wave * L, vV + wave * L, L, k, gather, sout ? sout + (pb + wave) * L : nullptr,
                              list + wave * kp, slotmap + wave * L, lane);
     }
-    __syncthreads();
-    // 5. kept rows from the registers
-    if (gather) {
-#pragma unroll
-      for (int c = 0; c < C; ++c) {
-        if (c < cb) {
-          char* dst = tout + (S + (pb + c) * k) * rowbytes + coff;
-#pragma unroll
-          for (int j = 0; j < NSC; ++j) {
-            const int s = c * NSC + j;
-            const int sl = slotmap[s * R + row0];
-            if (sl >= 0) st16_out(dst + (int64_t)sl * rowbytes, hold[s]);
-          }
-        }
+    lds_barrier();
+    if (iout)
+      for (int i = tid; i < cb * k; i += nthreads) {
+        const int c = i / k, j = i - c * k;  // (positions of a batch's chunks are contiguous in the output)
+        st4_out_at(iout + S + pb * k, (uint32_t)i * 4u, (uint32_t)(S + (pb + c) * L + list[c * kp + j]));
       }
-      if (iout)
-        for (int i = tid; i < cb * k; i += nthreads) {
-          const int c = i / k, j = i - c * k;
-          iout[S + (pb + c) * k + j] = (int32_t)(S + (pb + c) * L + list[c * kp + j]);
-        }
-    }
+    // The kept rows stay in the registers; the next sweep (or the flush below) stores them.
+    // The next batch rewrites the statistics and variances (last read before the barrier
+    // above) during its sweep, the slot map and the lists only after its own first barrier.
+    prev_pb = pb;
+    prev_nsb = nsb;
     pe = pb;
+    pb = next_pb;
+    nsb = next_nsb;
+    rows = next_rows;
     q ^= 1;
-    // no barrier here: the next batch writes the statistics and variances (last read before
-    // the barrier above) before its first barrier, the slot map and the lists after it
   }
+  static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
+    constexpr int s = decltype(step_tag)::value;
+    if (gather && s < prev_nsb) store_prev(s, s / NSC);
+  });
 }
 
 // ------------------------------------------------------------------------ host side
@@ -346,9 +403,9 @@ static hipError_t launch_hold_one(K kernel, const PassArgs& a, dim3 grid, size_t
 template <typename ET, bool LOCAL>
 static hipError_t launch_hold_v(const PassArgs& a, int nsc, dim3 grid, size_t lds, hipStream_t s) {
   switch (nsc) {
-    case 8: return launch_hold_one(hold_pass_kernel<ET, 16, 8, LOCAL>, a, grid, lds, s);
-    case 16: return launch_hold_one(hold_pass_kernel<ET, 16, 16, LOCAL>, a, grid, lds, s);
-    case 32: return launch_hold_one(hold_pass_kernel<ET, 16, 32, LOCAL>, a, grid, lds, s);
+    case 8: return launch_hold_one(hold_pass_kernel<ET, 8, LOCAL>, a, grid, lds, s);
+    case 16: return launch_hold_one(hold_pass_kernel<ET, 16, LOCAL>, a, grid, lds, s);
+    case 32: return launch_hold_one(hold_pass_kernel<ET, 32, LOCAL>, a, grid, lds, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -363,7 +420,7 @@ hipError_t launch_hold_pass(const PassArgs& a, hipStream_t s) {
   const int lpr = 16, nsc = hold_nsc(a.L, lpr), R = (kHoldWaves / 2) * (kWave / lpr);
   const int64_t nblocks = (int64_t)a.B * a.H * a.nseg;
   if (nblocks <= 0 || nblocks > 0x7fffffffLL || a.nseg < 1 || a.nseg > a.n_s) return hipErrorInvalidValue;
-  // offsets inside a batch are 32 bit: its rows must lie within 2 GiB
+  // per-lane offsets inside a step are 32 bit, and so are the step offsets of the first loads
   if (a.st * (int64_t)R * kHoldSteps >= (1LL << 31)) return hipErrorInvalidValue;
   const size_t lds = (size_t)hold_lds(a.D, kHoldSteps * R, a.k, kHoldSteps / nsc).total;
   const dim3 grid((unsigned)nblocks);

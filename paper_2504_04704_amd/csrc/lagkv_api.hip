@@ -168,11 +168,15 @@ int pick_segments_hold(const Norm& n, int64_t n_s) {
   return (int)(nseg < 1 ? 1 : nseg);
 }
 
-// Eq. 14-15 would need two passes over a chunk in the streaming kernel; the
-// register-resident kernel reads it once, so it is that variant's default where it applies.
+// The register-resident kernel is the default where it measures faster than the streaming
+// one: chunks of 512 rows of 256 bytes, whose K+V footprint (256 KiB) the streaming kernel
+// has to read a second time from beyond the L2 for the compaction (and, for Eq. 14-15, a
+// second time for the scoring as well).  Shorter chunks stay within the L2 between their two
+// reads, and the streaming kernel's several workgroups per CU hide the per-chunk selection
+// better than the single resident one.
 bool use_resident(const Norm& n) {
   if (n.variant == LAGKV_SCORE_L2 || !hold_supported(n.D, n.esize, n.L, n.k)) return false;
-  return n.hint.path == LAGKV_PATH_RESIDENT || (n.hint.path == LAGKV_PATH_AUTO && n.variant == LAGKV_SCORE_LOCAL);
+  return n.hint.path == LAGKV_PATH_RESIDENT || (n.hint.path == LAGKV_PATH_AUTO && n.L >= 512);
 }
 
 // Launch the one-shot fused kernel.

@@ -77,5 +77,36 @@ __device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
 }
 __device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// The same asynchronous row load written out, for kernels that keep loads in flight across
+// barriers: the compiler does not know of it and so never waits for it on its own (a load it
+// knows of is drained at the next fence).  Lane l's 16 bytes at sbase + lane_off are written
+// to LDS at lds_addr + 16*l; sbase and lds_addr are wave-uniform.  M0 carries the LDS address
+// (the compiler reserves M0 and re-loads it before each of its own uses; the s_nop covers the
+// wait state between the write of M0 and the load that reads it).
+__device__ __forceinline__ void dma_rows16(uint32_t lane_off, const char* sbase, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(lane_off), "s"(sbase), "s"(lds_addr)
+      : "memory");
+}
+
+// 4-byte store of an output position, issued like st16_out (not known to the compiler).
+__device__ __forceinline__ void st4_out(void* p, uint32_t v) {
+  asm volatile("global_store_dword %0, %1, off" ::"v"(p), "v"(v) : "memory");
+}
+// The same stores with a wave-uniform base and a 32-bit lane offset (one address register
+// instead of two).
+__device__ __forceinline__ void st16_out_at(char* sbase, uint32_t voff, const uint4& v) {
+  typedef uint32_t vec4_t __attribute__((ext_vector_type(4)));
+  const vec4_t q = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, %2 sc0 nt" ::"v"(voff), "v"(q), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void st4_out_at(void* sbase, uint32_t voff, uint32_t v) {
+  asm volatile("global_store_dword %0, %1, %2" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
+}
+
 
 }  // namespace lagkv

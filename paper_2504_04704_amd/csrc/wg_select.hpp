@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lds_dma.hpp"
 #include "wave_ops.hpp"
 
 namespace lagkv {
@@ -171,7 +172,8 @@ __device__ __forceinline__ void group_score_select(float* vK, const float* vV, i
   const float s = eK * (1.0f / tK) + eV * (1.0f / tV);
   if (live) {
     vK[tid] = s;
-    if (gout) gout[tid] = s;
+    // (a store the compiler does not know of, hence does not wait for at the barriers below)
+    if (gout) st4_out_at(gout, (uint32_t)tid * 4u, __float_as_uint(s));
   }
   if (do_select) group_topk(live ? ordered_key(s) : 0u, L, k, scratch, list, slotmap, tid, nw);
 }
