@@ -3,16 +3,19 @@
 
 A step is one whole pass of the hot path (score -> per-chunk top-k -> compaction,
 K, V and their original indices written) over one batch of synthetic KV that is
-already resident in HBM.  Default workload: the 128K-context headline
-configuration (Llama-3-8B-shaped bf16 cache, 32 layers x 8 KV heads x D=128, B=4,
-T=131072, S=16, L=512, r=0.25; 64 GiB scanned per pass).
+already resident in HBM.  Headline workload: the 128K-context configuration
+(Llama-3-8B-shaped bf16 cache, 32 layers x 8 KV heads x D=128, B=4, T=131072, S=16,
+L=512, r=0.25; 64 GiB scanned per pass).
 
 Prints ONE JSON line: metric/value/unit (KV tokens per second, a token being one
 (batch, position) over all layers and heads), ms_per_step, config, `roofline` (achieved
-algorithmic GB/s of the kernel against the 8 TB/s HBM peak, measured with HIP events; HBM
-traffic from the recorded counters) and `cpu_baseline` (the fp64 oracle on a sample of the
-same streams).  `--workload decode` times the decode-time step (config 5) instead,
-`--variant` the LocalKV / L2-norm scoring ablations.
+algorithmic GB/s of the kernel against the 8 TB/s HBM peak, measured with HIP events on the
+launch stream; median/p10/p90; the figure on the first allocation and the median over the
+placement trials beside the kept one; HBM traffic from the recorded counters) and
+`cpu_baseline` (the fp64 oracle on a sample of the same streams).  The default run also times
+the 16K and 64K configurations and the decode-time step (config 5, all 64 rounds) and reports
+them in `config.other_workloads`.  `--workload compress|decode|copy` runs one of them alone (the
+form the profiler commands use), `--variant` the LocalKV / L2-norm scoring ablations.
 """
 from __future__ import annotations
 
@@ -29,12 +32,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+DEV = "cuda:0"
 
 
 def algorithmic_bytes(streams: int, T: int, T_out: int, D: int, esize: int, with_idx: bool = True) -> int:
     """Each input element read once, each kept element written once (K and V), plus the
     int32 source index of every output row."""
     return streams * (2 * esize * D * (T + T_out) + (4 * T_out if with_idx else 0))
+
+
+def decode_algorithmic_bytes(streams: int, L: int, m: int, k: int, D: int, esize: int) -> int:
+    """One decode call per stream, dense layout with the append fused in: read the L + m tail
+    rows and the L new rows, write the k kept rows and the L + m rows of the slid tail (K and V)."""
+    return streams * ((L + m + L) + (k + L + m)) * D * esize * 2
 
 
 def read_traffic(name: str):
@@ -47,10 +57,20 @@ def read_traffic(name: str):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline_compress(K, V, cfg, stream_ids, layers_x_heads: int):
+def quantiles(xs):
+    s = sorted(xs)
+    q = lambda f: s[min(len(s) - 1, max(0, int(round(f * (len(s) - 1)))))]
+    return {"median": q(0.5), "p10": q(0.1), "p90": q(0.9), "min": s[0], "mean": sum(s) / len(s)}
+
+
+def host_threads() -> int:
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def cpu_baseline_compress(K, V, cfg, stream_ids, layers_x_heads: int, n_single: int):
     """Times the oracle (as it stands) on a bounded sample of streams copied from the
-    device: single thread, then one thread per stream over the host cores."""
-    import numpy as np
+    device: single thread on the first n_single, then one thread per stream over the host
+    cores (NumPy releases the GIL only inside its kernels, so the threads scale poorly)."""
     import torch
     from oracle import lagkv_oracle as O
 
@@ -61,15 +81,16 @@ def cpu_baseline_compress(K, V, cfg, stream_ids, layers_x_heads: int):
 
     def one(kv):
         k, v = kv
-        return O.compress(k.double().numpy(), v.double().numpy(), cfg.S, cfg.L, cfg.r,
-                          raw=(k.view(torch.int16).numpy(), v.view(torch.int16).numpy()))[2].shape[0]
+        raw = (k.view(torch.int16).numpy(), v.view(torch.int16).numpy()) if k.dtype == torch.bfloat16 \
+            else (k.numpy(), v.numpy())
+        return O.compress(k.double().numpy(), v.double().numpy(), cfg.S, cfg.L, cfg.r, raw=raw)[2].shape[0]
 
-    n1 = max(1, len(host) // 4)
+    n1 = max(1, min(n_single, len(host)))
     t0 = time.perf_counter()
     for kv in host[:n1]:
         one(kv)
     t_single = time.perf_counter() - t0
-    threads = max(1, min(16, os.cpu_count() or 1, len(host)))
+    threads = min(host_threads(), len(host))
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:
         list(ex.map(one, host))
@@ -77,36 +98,85 @@ def cpu_baseline_compress(K, V, cfg, stream_ids, layers_x_heads: int):
     tok_single = n1 * cfg.T / t_single / layers_x_heads
     tok_multi = len(host) * cfg.T / t_multi / layers_x_heads
     best_multi = tok_multi >= tok_single
+    whole = len(host) == cfg.streams
     return {
         "value": tok_multi if best_multi else tok_single,
         "unit": "tokens/s",
         "cores": threads if best_multi else 1,
         "kind": "oracle",
         "sample": f"{len(host)} of {cfg.streams} whole (layer,batch,head) streams of the same cache, "
-                  f"copied from the device; fp64 NumPy oracle; extrapolated to all streams; "
+                  f"copied from the device; fp64 NumPy oracle; "
+                  f"{'every stream timed' if whole else 'extrapolated to all streams'}; "
                   f"single thread on {n1} streams: {tok_single:.1f} tokens/s, "
-                  f"{threads} threads on {len(host)} streams: {tok_multi:.1f} tokens/s",
+                  f"{threads} threads (one stream each; GIL- and memory-bound, they scale poorly) on "
+                  f"{len(host)} streams: {tok_multi:.1f} tokens/s",
     }
 
 
-def bench_compress(args):
+def timed_steps(step, steps: int, warmup: int):
+    """W untimed steps, then K steps: wall time bracketed by synchronisation on both sides and
+    one HIP-event pair per step on the stream the kernels are launched on."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall * 1e3 / steps, [s.elapsed_time(e) for s, e in zip(starts, ends)]
+
+
+def copy_rate_gbs(src, dst, n=3):
+    """Read+write rate of a plain device copy between two of the workload's own buffers
+    (dst.numel() elements): the yardstick SURVEY-style rooflines call 'copy bandwidth'."""
+    import torch
+    flat_s, flat_d = src.reshape(-1), dst.reshape(-1)
+    cnt = min(flat_s.numel(), flat_d.numel())
+    flat_d[:cnt].copy_(flat_s[:cnt])
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(n):
+        flat_d[:cnt].copy_(flat_s[:cnt])
+    e.record()
+    torch.cuda.synchronize()
+    return 2 * cnt * src.element_size() / (s.elapsed_time(e) / n * 1e-3) / 1e9
+
+
+def kernel_name(cfg, variant: str, path: int) -> str:
+    if variant == "l2":
+        return "split_pass_kernel"
+    if path == 3 or (path == 0 and cfg.L >= 512 and cfg.D * 2 == 256):
+        return "hold_pass_kernel"
+    return "split_pass_kernel"
+
+
+def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None, cpu_streams=None,
+                   cpu_single=None, with_copy=True):
     import torch
     from paper_2504_04704_amd import lagkv, synth
 
-    cfg = synth.CONFIGS[args.config]
-    dev = "cuda:0"
+    cfg = synth.CONFIGS[cfg_name or args.config]
+    steps = steps or args.steps
+    warmup = args.warmup if warmup is None else warmup
+    placements = args.placements if placements is None else placements
     lagkv.load()
     launch = lagkv.launch_hint(args.path, args.waves, args.segments, args.order, args.select)
     variant = {"lag": lagkv.SCORE_LAG, "local": lagkv.SCORE_LOCAL, "l2": lagkv.SCORE_L2}[args.variant]
 
     def build_working_set():
-        K, V = synth.make_kv(cfg, device=dev)
+        K, V = synth.make_kv(cfg, device=DEV)
         p = lagkv.params_for(K, cfg.S, cfg.L, cfg.r, variant=variant, launch=launch)
         pl = lagkv.plan(p, cfg.T)
         Bf, H, T, D = K.shape
-        Ko = torch.empty((Bf, H, pl.T_out, D), dtype=K.dtype, device=dev)
+        Ko = torch.empty((Bf, H, pl.T_out, D), dtype=K.dtype, device=DEV)
         Vo = torch.empty_like(Ko)
-        idx = torch.empty((Bf, H, pl.T_out), dtype=torch.int32, device=dev)
+        idx = torch.empty((Bf, H, pl.T_out), dtype=torch.int32, device=DEV)
         return K, V, Ko, Vo, idx, p, pl
 
     def quick_ms(ws_set, n=3):
@@ -122,20 +192,20 @@ def bench_compress(args):
 
     # Placement (set-up, not part of any step).  The time of this pass depends on where the
     # driver puts the buffers physically: the same kernel on the same bytes runs in one of a few
-    # distinct speeds (about 15.5, 16.6 or 17.3 ms on the 128K workload) from one allocation of
-    # the working set to the next, the first allocation on a freshly started GPU always being the
-    # slowest.  A server allocates its cache once and keeps it, so it can afford to look for a
-    # good placement at start-up; the bench does the same: it builds the working set
-    # `--placements` times, times three launches on each, and keeps the fastest set (the others
-    # are released).  Every trial is reported in config.placement_trials_ms; the K timed steps
-    # then all run on the buffers that were kept.
+    # distinct speeds from one allocation of the working set to the next, the first allocation
+    # on a freshly started GPU always being the slowest.  A server allocates its cache once and
+    # keeps it, so it can afford to look for a good placement at start-up; the bench does the
+    # same: it builds the working set `--placements` times, times three launches on each, and
+    # keeps the fastest set (the others are released).  Every trial is reported in
+    # config.placement_trials_ms, and roofline carries the first-allocation and the
+    # median-of-trials fractions beside the kept one; the K timed steps all run on the kept buffers.
     trials = []
     best = None
     t0 = time.perf_counter()
-    for _ in range(1 if args.no_page_warmup else max(1, args.placements)):
+    for _ in range(1 if args.no_page_warmup else max(1, placements)):
         cand = build_working_set()
         ms = quick_ms(cand)
-        trials.append(round(ms, 3))
+        trials.append(round(ms, 4))
         if best is None or ms < best[0]:
             best = (ms, cand)
         del cand
@@ -148,60 +218,91 @@ def bench_compress(args):
 
     # caller-owned workspace (only the three-kernel path uses it): nothing is allocated per step
     nws = lagkv.workspace_bytes(p, cfg.T)
-    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=DEV)
 
     def step():
         lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=variant, out=(Ko, Vo), idx_out=idx, ws=ws, launch=launch)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record()
-        step()
-        ends[i].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
-    kern_avg_ms = sum(kern_ms) / len(kern_ms)
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step, kern_ms = timed_steps(step, steps, warmup)
+    q = quantiles(kern_ms)
     tokens = cfg.B * cfg.T                      # one token = one (batch, position) over all layers and heads
     alg = algorithmic_bytes(cfg.streams, cfg.T, pl.T_out, cfg.D, K.element_size())
-    kernel = "split_pass_kernel"
     if args.variant == "l2":
         # Eq. 16 scores from K alone: V is read only where it is kept
         alg = cfg.streams * (K.element_size() * cfg.D * (cfg.T + 3 * pl.T_out) + 4 * pl.T_out)
-        kernel = "staged_score_kernel + select_kernel + gather_rows_kernel x2"
-    achieved = alg / (kern_avg_ms * 1e-3) / 1e9
-    traffic = read_traffic(f"split_pass_{cfg.name}_traffic.txt") if args.variant == "lag" else None
+    gbs = lambda ms: alg / (ms * 1e-3) / 1e9
+    kernel = kernel_name(cfg, args.variant, args.path)
+    traffic = read_traffic(f"{kernel.replace('_kernel', '')}_{cfg.name}_traffic.txt") if args.variant == "lag" else None
+    tq = quantiles(trials)
+    roof = {"bound": "hbm", "achieved": gbs(q["mean"]), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": gbs(q["mean"]) / HBM_PEAK_GBS, "traffic": traffic,
+            "kernel": kernel, "kernel_ms_avg": q["mean"], "kernel_ms_median": q["median"],
+            "kernel_ms_p10": q["p10"], "kernel_ms_p90": q["p90"], "kernel_ms_min": q["min"],
+            "frac_median": gbs(q["median"]) / HBM_PEAK_GBS,
+            "frac_first_alloc": gbs(trials[0]) / HBM_PEAK_GBS,
+            "frac_median_of_trials": gbs(tq["median"]) / HBM_PEAK_GBS,
+            "algorithmic_bytes": alg,
+            "traffic_over_algorithmic": (traffic / alg) if traffic else None}
     res = {
         "metric": "kv_tokens_compressed_per_sec_128k_ctx" if cfg.T == 131072 else "kv_tokens_compressed_per_sec",
         "value": tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "B": cfg.B, "H_kv": cfg.H, "D": cfg.D,
-                   "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype, "variant": args.variant,
-                   "T_out": int(pl.T_out), "streams": cfg.streams,
+                   "T": cfg.T, "S": cfg.S, "L": cfg.L, "r": cfg.r, "kv_dtype": cfg.dtype, "compute_dtype": "f32",
+                   "variant": args.variant, "T_out": int(pl.T_out), "streams": cfg.streams,
                    "placement_trials_ms": trials,
                    "head_tokens_per_s": cfg.streams * cfg.T / (ms_per_step * 1e-3)},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": kernel, "kernel_ms_avg": kern_avg_ms,
-                     "kernel_ms_min": min(kern_ms), "algorithmic_bytes": alg},
+        "roofline": roof,
     }
     if not args.no_cpu and args.variant == "lag":
-        ids = synth.stream_sample(cfg.streams, args.cpu_streams)
-        res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H)
+        ids = synth.stream_sample(cfg.streams, cpu_streams or args.cpu_streams)
+        res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H,
+                                                    cpu_single or max(1, len(ids) // 4))
+    if with_copy:
+        copy = copy_rate_gbs(K, Ko)      # (overwrites the output buffers: the last thing done with them)
+        roof["copy_gbs"] = copy
+        roof["frac_of_copy"] = roof["achieved"] / copy
     return res
 
 
-def bench_decode(args):
+def cpu_baseline_decode(cache, cfg, Kn, Vn, stream_ids):
+    """The oracle's recursive step (IncrementalCache.append of one lag) on a sample of streams,
+    starting from the rows the device cache holds for them."""
+    import numpy as np
+    from oracle import lagkv_oracle as O
+
+    n = cache.length
+    todo = []
+    for s in stream_ids:
+        b, h = divmod(s, cfg.H)
+        todo.append((cache.K[b, h, :n].cpu().double().numpy(), cache.V[b, h, :n].cpu().double().numpy(),
+                     cache.pos[b, h, :n].cpu().numpy(), Kn[b, h].cpu().double().numpy(),
+                     Vn[b, h].cpu().double().numpy()))
+    n_chunks = (cache.n_static - cfg.S) // O.keep_count(cfg.L, cfg.r)
+
+    def one(t):
+        k, v, pos, kn, vn = t
+        c = O.IncrementalCache.from_state(k, v, pos, cache.n_seen, n_chunks, cfg.S, cfg.L, cfg.r)
+        return c.append(kn, vn)
+
+    threads = min(host_threads(), len(todo))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        rounds = list(ex.map(one, todo))
+    dt = time.perf_counter() - t0
+    assert all(r == 1 for r in rounds)
+    tok = len(todo) * cfg.L / dt / (cfg.layers * cfg.H)
+    return {"value": tok, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"one append of {cfg.L} rows to {len(todo)} of {cfg.streams} streams (their device cache "
+                      f"copied to the host, fp64 NumPy IncrementalCache.append, {threads} threads); "
+                      f"extrapolated to all streams"}
+
+
+def bench_decode(args, steps=None, warmup=None):
     """Config 5: start from a compressed T=32768 cache at batch B, append L tokens per
     sequence per call; reports per-call latency and sustained tokens/s."""
     import torch
@@ -210,63 +311,84 @@ def bench_decode(args):
     cfg = synth.CONFIGS["cfg5_decode_b32"]
     if args.decode_batch:
         cfg = cfg.scaled(B=args.decode_batch)
-    dev = "cuda:0"
+    steps = steps or args.steps
+    warmup = args.warmup if warmup is None else warmup
     lagkv.load()
-    rounds = args.steps + args.warmup
+    launch = lagkv.launch_hint(args.path, args.waves, 0, 0, args.select)
+    variant = {"lag": lagkv.SCORE_LAG, "local": lagkv.SCORE_LOCAL, "l2": lagkv.SCORE_L2}[args.variant]
+    rounds = 2 * steps + warmup
     pl = lagkv.plan(lagkv.make_params(cfg.layers * cfg.B, cfg.H, cfg.D, cfg.S, cfg.L, cfg.r), cfg.T)
     cap = pl.T_out + rounds * pl.k + cfg.L
-    cache = lagkv.Cache(cfg.layers * cfg.B, cfg.H, cfg.D, cap, cfg.S, cfg.L, cfg.r, track_positions=True)
+    cache = lagkv.Cache(cfg.layers * cfg.B, cfg.H, cfg.D, cap, cfg.S, cfg.L, cfg.r, track_positions=True,
+                        variant=variant, launch=launch)
     # build the compressed starting cache layer by layer (the uncompressed one is 128 GiB at B=32)
-    one = cfg.scaled(layers=1)
-    Kl = torch.empty((cfg.B, cfg.H, cfg.T, cfg.D), dtype=torch.bfloat16, device=dev)
+    Kl = torch.empty((cfg.B, cfg.H, cfg.T, cfg.D), dtype=torch.bfloat16, device=DEV)
     Vl = torch.empty_like(Kl)
     for l in range(cfg.layers):
         synth.fill_layer(cfg, synth.MASTER_SEED, l, Kl, Vl)
-        comp = lagkv.compress(Kl, Vl, cfg.S, cfg.L, cfg.r)
+        comp = lagkv.compress(Kl, Vl, cfg.S, cfg.L, cfg.r, variant=variant)
         sl = slice(l * cfg.B, (l + 1) * cfg.B)
         cache.K[sl, :, :pl.T_out].copy_(comp.K)
         cache.V[sl, :, :pl.T_out].copy_(comp.V)
         cache.pos[sl, :, :pl.T_out].copy_(comp.idx)
-    del Kl, Vl, comp, one
+    del Kl, Vl, comp
     cache.mark_compressed(cfg.T)
     torch.cuda.synchronize()
-    new = [synth.make_new_tokens(cfg, cfg.L, i % 4, device=dev) for i in range(4)]
+    new = [synth.make_new_tokens(cfg, cfg.L, i % 4, device=DEV) for i in range(4)]
+    cpu = None
+    if not args.no_cpu and args.variant == "lag":
+        cpu = cpu_baseline_decode(cache, cfg, new[0][0], new[0][1], synth.stream_sample(cfg.streams, 64))
+    # `steps` calls one at a time (synchronised before and after: the latency a decode loop sees),
+    # then `steps` more calls queued back to back with an event between them: the duration of
+    # the kernel itself, free of the idle-queue start-up of a lone launch
     lat = []
-    for i in range(rounds):
+    for i in range(warmup + steps):
         Kn, Vn = new[i % 4]
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        s.record()
         cache.append_and_compress(Kn, Vn)
-        e.record()
         torch.cuda.synchronize()
-        if i >= args.warmup:
-            lat.append(((time.perf_counter() - t0) * 1e3, s.elapsed_time(e)))
-    wall = sorted(x[0] for x in lat)
-    dev_ms = sorted(x[1] for x in lat)
+        if i >= warmup:
+            lat.append((time.perf_counter() - t0) * 1e3)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for i in range(steps):
+        Kn, Vn = new[i % 4]
+        cache.append_and_compress(Kn, Vn)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    dev = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    wall = sorted(lat)
+    dq = quantiles(dev)
     ms = sum(wall) / len(wall)
     tokens = cfg.B * cfg.L
-    # per stream and call, dense layout with the append fused in: read the L + m tail rows and the
-    # L new rows, write the k kept rows and the L + m rows of the slid tail
-    rowb = cfg.D * 2 * 2
     m = (cfg.T - cfg.S) % cfg.L
-    alg = cfg.streams * ((cfg.L + m + cfg.L) + (pl.k + cfg.L + m)) * rowb
-    return {
+    alg = decode_algorithmic_bytes(cfg.streams, cfg.L, m, pl.k, cfg.D, 2)
+    if args.variant == "l2":   # the chunk's V rows are read only where kept
+        alg -= cfg.streams * (cfg.L - pl.k) * cfg.D * 2
+    res = {
         "metric": "decode_append_and_compress_tokens_per_sec", "value": tokens / (ms * 1e-3),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "streams": cfg.streams, "T0": cfg.T, "L": cfg.L,
-                   "r": cfg.r, "n_new": cfg.L, "latency_ms_p50": wall[len(wall) // 2],
+                   "r": cfg.r, "n_new": cfg.L, "variant": args.variant, "kv_dtype": cfg.dtype, "compute_dtype": "f32",
+                   "latency_ms_p50": wall[len(wall) // 2],
                    "latency_ms_p99": wall[min(len(wall) - 1, int(len(wall) * 0.99))],
-                   "device_ms_p50": dev_ms[len(dev_ms) // 2], "final_length": cache.length},
-        "roofline": {"bound": "hbm", "achieved": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9,
+                   "device_ms_p50": dq["median"], "device_ms_p10": dq["p10"], "device_ms_p90": dq["p90"],
+                   "calls_timed_one_by_one": steps, "calls_timed_back_to_back": steps,
+                   "length_after_the_first_steps": int(pl.T_out + (warmup + steps) * pl.k),
+                   "final_length": cache.length},
+        "roofline": {"bound": "hbm", "achieved": alg / (dq["mean"] * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": alg / (dev_ms[len(dev_ms) // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": read_traffic("decode_step_cfg5_decode_b32.md") if cfg.B == 32 else None,
-                     "kernel": "decode_step_kernel", "algorithmic_bytes": alg},
+                     "frac": alg / (dq["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "frac_median": alg / (dq["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": read_traffic("decode_step_cfg5_decode_b32.md") if (cfg.B == 32 and args.variant == "lag") else None,
+                     "kernel": "decode_step_kernel", "kernel_ms_avg": dq["mean"], "algorithmic_bytes": alg},
     }
+    if cpu:
+        res["cpu_baseline"] = cpu
+    return res
 
 
 def bench_copy(args):
@@ -276,10 +398,9 @@ def bench_copy(args):
     import torch
     from paper_2504_04704_amd import lagkv
 
-    dev = "cuda:0"
     lagkv.load()
-    K = torch.randn((64, 8, 8192, 128), device=dev).to(torch.bfloat16)
-    V = torch.randn((64, 8, 8192, 128), device=dev).to(torch.bfloat16)
+    K = torch.randn((64, 8, 8192, 128), device=DEV).to(torch.bfloat16)
+    V = torch.randn((64, 8, 8192, 128), device=DEV).to(torch.bfloat16)
     Ko, Vo = torch.empty_like(K), torch.empty_like(V)
     nbytes = K.numel() * 2
     evs = []
@@ -301,14 +422,57 @@ def bench_copy(args):
                        "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes}}
 
 
+def summary_of(res):
+    """The entry of config.other_workloads for one of the secondary workloads."""
+    roof, cfg = res["roofline"], res["config"]
+    out = {"workload": cfg["workload"], "metric": res["metric"], "value": res["value"], "unit": res["unit"],
+           "steps": res["steps"], "ms": roof.get("kernel_ms_median", cfg.get("device_ms_p50")),
+           "ms_p10": roof.get("kernel_ms_p10", cfg.get("device_ms_p10")),
+           "ms_p90": roof.get("kernel_ms_p90", cfg.get("device_ms_p90")),
+           "ms_per_step": res["ms_per_step"], "frac": roof["frac"], "achieved_gbs": roof["achieved"],
+           "algorithmic_bytes": roof["algorithmic_bytes"], "traffic": roof["traffic"], "kernel": roof["kernel"],
+           "cpu_baseline": res.get("cpu_baseline")}
+    for key in ("latency_ms_p50", "latency_ms_p99", "length_after_the_first_steps", "final_length", "placement_trials_ms",
+                "streams", "T", "L", "r", "B"):
+        if key in cfg:
+            out[key] = cfg[key]
+    for key in ("frac_first_alloc", "frac_median_of_trials", "frac_of_copy"):
+        if key in roof:
+            out[key] = roof[key]
+    return out
+
+
+def bench_all(args):
+    """The headline workload, then (unless --only-headline) configurations 2 and 3 and the decode step."""
+    import torch
+    res = bench_compress(args)
+    if args.only_headline:
+        return res
+    torch.cuda.empty_cache()
+    others = []
+    t0 = time.perf_counter()
+    # the 16K cache in full and a quarter of the 64K one on the host: a few seconds of oracle each
+    for name, cpu_n in (("cfg2_llama8b_16k", 256), ("cfg3_llama8b_64k", 64)):
+        r = bench_compress(args, cfg_name=name, steps=max(args.steps, 20), warmup=3, placements=2,
+                           cpu_streams=cpu_n, cpu_single=8)
+        others.append(summary_of(r))
+        torch.cuda.empty_cache()
+    r = bench_decode(args, steps=64, warmup=2)      # the 64 rounds the configuration names
+    others.append(summary_of(r))
+    print(f"[bench] other workloads in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    res["config"]["other_workloads"] = others
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["compress", "decode", "copy"], default="compress")
+    ap.add_argument("--workload", choices=["all", "compress", "decode", "copy"], default="all")
+    ap.add_argument("--only-headline", action="store_true", help="with --workload all: skip the secondary workloads")
     ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline legs")
     ap.add_argument("--cpu-streams", type=int, default=96,
                     help="streams the CPU oracle baseline is timed on (about 10-15 s of CPU work)")
     ap.add_argument("--placements", type=int, default=6,
@@ -332,8 +496,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
-    res = {"compress": bench_compress, "decode": bench_decode, "copy": bench_copy}[args.workload](args)
-    print(json.dumps(res), flush=True)
+    if args.workload == "compress":
+        args.only_headline = True
+    run = {"all": bench_all, "compress": bench_all, "decode": bench_decode, "copy": bench_copy}[args.workload]
+    print(json.dumps(run(args)), flush=True)
 
 
 if __name__ == "__main__":

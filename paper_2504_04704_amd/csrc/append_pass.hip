@@ -15,40 +15,22 @@
 
 namespace lagkv {
 
-// Running per-channel min/max of the lane's VEC channels (Eq. 7-8), K and V.
+// K and V statistics side by side for the kernel whose lanes handle both tensors: the running
+// per-channel min/max (Eq. 7-8) and the form Eq. 9 consumes, one TStats / TRef per tensor.
 template <int VEC>
 struct ChanStats {
-  float mnK[VEC], mxK[VEC], mnV[VEC], mxV[VEC];
+  TStats<VEC> K, V;
   __device__ __forceinline__ void reset() {
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      mnK[j] = INFINITY;
-      mxK[j] = -INFINITY;
-      mnV[j] = INFINITY;
-      mxV[j] = -INFINITY;
-    }
+    K.reset();
+    V.reset();
   }
 };
-
-// Reference statistics in the form the normalisation of Eq. 9 consumes:
-// zbar = (x - mn) * iv with iv = 1/(max-min), or 0 for a constant channel.
-// bias = sum_j -(mn_j*iv_j) seeds the (accuracy-insensitive) mean accumulation.
 template <int VEC>
 struct RefStats {
-  float mnK[VEC], ivK[VEC], mnV[VEC], ivV[VEC];
-  float biasK, biasV;
+  TRef<VEC> K, V;
   __device__ __forceinline__ void from(const ChanStats<VEC>& s) {
-    biasK = 0.f;
-    biasV = 0.f;
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      mnK[j] = s.mnK[j];
-      ivK[j] = inv_range(s.mnK[j], s.mxK[j]);
-      mnV[j] = s.mnV[j];
-      ivV[j] = inv_range(s.mnV[j], s.mxV[j]);
-      biasK -= mnK[j] * ivK[j];
-      biasV -= mnV[j] * ivV[j];
-    }
+    K.from(s.K);
+    V.from(s.V);
   }
 };
 
@@ -103,26 +85,26 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
       if constexpr (STATS) {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
-          acc.mnK[j] = fminf(fminf(acc.mnK[j], x0[j]), x1[j]);
-          acc.mxK[j] = fmaxf(fmaxf(acc.mxK[j], x0[j]), x1[j]);
+          acc.K.mn[j] = fminf(fminf(acc.K.mn[j], x0[j]), x1[j]);
+          acc.K.mx[j] = fmaxf(fmaxf(acc.K.mx[j], x0[j]), x1[j]);
         }
       }
       if constexpr (SCORE) {
-        sgK0 = token_var<LPR, VEC>(x0, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
-        sgK1 = token_var<LPR, VEC>(x1, ref.mnK, ref.ivK, ref.biasK, inv_D, inv_dof);
+        sgK0 = token_var<LPR, VEC>(x0, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof);
+        sgK1 = token_var<LPR, VEC>(x1, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof);
       }
       unpack<ET>(vq[u], x0);
       unpack<ET>(vq[u + 1], x1);
       if constexpr (STATS) {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
-          acc.mnV[j] = fminf(fminf(acc.mnV[j], x0[j]), x1[j]);
-          acc.mxV[j] = fmaxf(fmaxf(acc.mxV[j], x0[j]), x1[j]);
+          acc.V.mn[j] = fminf(fminf(acc.V.mn[j], x0[j]), x1[j]);
+          acc.V.mx[j] = fmaxf(fmaxf(acc.V.mx[j], x0[j]), x1[j]);
         }
       }
       if constexpr (SCORE) {
-        sgV0 = token_var<LPR, VEC>(x0, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
-        sgV1 = token_var<LPR, VEC>(x1, ref.mnV, ref.ivV, ref.biasV, inv_D, inv_dof);
+        sgV0 = token_var<LPR, VEC>(x0, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof);
+        sgV1 = token_var<LPR, VEC>(x1, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof);
         if (g.cl == 0) {
           if (r[u] < L) {
             sK[r[u]] = sgK0;
@@ -149,10 +131,10 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
   for (int m = LPR; m < kWave; m <<= 1) {
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
-      acc.mnK[j] = fminf(acc.mnK[j], __shfl_xor(acc.mnK[j], m));
-      acc.mxK[j] = fmaxf(acc.mxK[j], __shfl_xor(acc.mxK[j], m));
-      acc.mnV[j] = fminf(acc.mnV[j], __shfl_xor(acc.mnV[j], m));
-      acc.mxV[j] = fmaxf(acc.mxV[j], __shfl_xor(acc.mxV[j], m));
+      acc.K.mn[j] = fminf(acc.K.mn[j], __shfl_xor(acc.K.mn[j], m));
+      acc.K.mx[j] = fmaxf(acc.K.mx[j], __shfl_xor(acc.K.mx[j], m));
+      acc.V.mn[j] = fminf(acc.V.mn[j], __shfl_xor(acc.V.mn[j], m));
+      acc.V.mx[j] = fmaxf(acc.V.mx[j], __shfl_xor(acc.V.mx[j], m));
     }
   }
   if (g.nw > 1) {
@@ -160,10 +142,10 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
       float* w = statbuf + (size_t)g.wave * 4 * D + g.cl * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
-        w[j] = acc.mnK[j];
-        w[D + j] = acc.mxK[j];
-        w[2 * D + j] = acc.mnV[j];
-        w[3 * D + j] = acc.mxV[j];
+        w[j] = acc.K.mn[j];
+        w[D + j] = acc.K.mx[j];
+        w[2 * D + j] = acc.V.mn[j];
+        w[3 * D + j] = acc.V.mx[j];
       }
     }
     __syncthreads();
@@ -171,10 +153,10 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
       const float* rd = statbuf + (size_t)w * 4 * D + g.cl * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
-        acc.mnK[j] = fminf(acc.mnK[j], rd[j]);
-        acc.mxK[j] = fmaxf(acc.mxK[j], rd[j + D]);
-        acc.mnV[j] = fminf(acc.mnV[j], rd[j + 2 * D]);
-        acc.mxV[j] = fmaxf(acc.mxV[j], rd[j + 3 * D]);
+        acc.K.mn[j] = fminf(acc.K.mn[j], rd[j]);
+        acc.K.mx[j] = fmaxf(acc.K.mx[j], rd[j + D]);
+        acc.V.mn[j] = fminf(acc.V.mn[j], rd[j + 2 * D]);
+        acc.V.mx[j] = fmaxf(acc.V.mx[j], rd[j + 3 * D]);
       }
     }
   } else {
@@ -431,6 +413,19 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
     for (int v = tid; v < n_all; v += nthreads)
       ptail[v] = v < n_tail ? pc[v] : (int32_t)(a.n_seen + (v - n_tail));
 
+  // 0. the first PF steps of the chunk (all of it for L <= PF * R) are requested right away,
+  // so that they travel together with the reference rows instead of after the first barrier
+  constexpr int PF = 8;
+  uint4 cq[PF];
+  const bool scores_rows = !l2 || tensor == 0;   // Eq. 16 reads only the keys of the chunk
+  if (scores_rows) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int r = row0 + u * R;
+      if (u < n_iter) cq[u] = ld16(src(r < L ? r : L - 1));
+    }
+  }
+
   // 1. reference chunk (tail rows [L,2L)): statistics, rows parked in LDS
   TStats<VEC> acc;
   acc.reset();
@@ -486,8 +481,25 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
 
   // 2. the chunk (tail rows [0,L)): channel variance of every token (Eq. 9-10), or, for
   // Eq. 16, minus the key norm (the V wavefronts then read nothing here)
-  if (!l2 || tensor == 0) {
-    for (int it = 0; it < n_iter; it += U) {
+  auto score_row = [&](const uint4& q, int r) __attribute__((always_inline)) {
+    float x[VEC];
+    unpack<ET>(q, x);
+    float v;
+    if (l2) {
+      float ss = 0.f;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
+      v = -sqrtf(group_sum<LPR>(ss));
+    } else {
+      v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+    }
+    if (cl == 0 && r < L) myvar[r] = v;
+  };
+  if (scores_rows) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+      if (u < n_iter) score_row(cq[u], row0 + u * R);
+    for (int it = PF; it < n_iter; it += U) {
       uint4 q[U];
       int r[U];
 #pragma unroll
@@ -496,21 +508,18 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
         q[u] = ld16(src(r[u] < L ? r[u] : L - 1));
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float x[VEC];
-        unpack<ET>(q[u], x);
-        float v;
-        if (l2) {
-          float ss = 0.f;
-#pragma unroll
-          for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
-          v = -sqrtf(group_sum<LPR>(ss));
-        } else {
-          v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-        }
-        if (cl == 0 && r[u] < L) myvar[r[u]] = v;
-      }
+      for (int u = 0; u < U; ++u) score_row(q[u], r[u]);
     }
+  }
+  // 2b. the rows behind the reference chunk (tail rows [2L, n_all)) are requested now and stored
+  // at the end: their flight overlaps the selection.  (Reads of this stream's rows all precede
+  // its first store except the kept rows, which are read before the barrier of step 3.)
+  const int nrem = n_all - 2 * L;
+  uint4 rq[PF];
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int r = u * R + row0;
+    if (r < nrem) rq[u] = ld16_last(src(2 * L + r));
   }
   if (group_sel && l2) group_sel_clear(selbuf, tid, nthreads);
   __syncthreads();
@@ -545,9 +554,15 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   // old place only
   for (int r = row0; r < L; r += R)
     st16_out(ct + (int64_t)(k + r) * rowbytes, *reinterpret_cast<const uint4*>(mystash + (size_t)r * rowbytes));
-  // 5. the rest of the tail, rows [2L, n_all) -> [k+L, ..), batch by batch as in 3.
-  const int nrem = n_all - 2 * L;
-  for (int r0 = 0; r0 < nrem; r0 += UB * R) {
+  // 5. the rest of the tail, rows [2L, n_all) -> [k+L, ..): the first PF steps from the registers
+  // (requested in 2b; their destinations lie below every row still to be read), what is left
+  // batch by batch as in 3.
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int r = u * R + row0;
+    if (r < nrem) st16_out(ct + (int64_t)(k + L + r) * rowbytes, rq[u]);
+  }
+  for (int r0 = PF * R; r0 < nrem; r0 += UB * R) {
     uint4 g[UB];
 #pragma unroll
     for (int u = 0; u < UB; ++u) {

@@ -137,14 +137,14 @@ int split_nw(const Norm& n) {
 }
 
 // Streams are cut into segments only when there are too few of them to fill the chip: the
-// target is 2 workgroups per CU (256 CUs) of 8 wavefronts, 3 of 4, 4 of 2 (measured optima;
+// target is 2 workgroups per CU (256 CUs) of 8 wavefronts, 3 of 4, 6 of 2 (measured optima;
 // every segment reads one extra chunk for its first reference), and segments keep >= 4 chunks.
 int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   int64_t nseg;
   if (n.hint.nseg) {
     nseg = n.hint.nseg;
   } else {
-    const int64_t capacity = 256 * (nw >= 8 ? 2 : nw >= 4 ? 3 : 4);
+    const int64_t capacity = 256 * (nw >= 8 ? 2 : nw >= 4 ? 3 : 6);
     nseg = n.streams >= capacity ? 1 : (capacity + n.streams - 1) / n.streams;
     const int64_t cap = n_s / 4 > 1 ? n_s / 4 : 1;
     if (nseg > cap) nseg = cap;

@@ -102,7 +102,10 @@ __device__ __forceinline__ void st4_out(void* p, uint32_t v) {
 __device__ __forceinline__ void st16_out_at(char* sbase, uint32_t voff, const uint4& v) {
   typedef uint32_t vec4_t __attribute__((ext_vector_type(4)));
   const vec4_t q = {v.x, v.y, v.z, v.w};
-  asm volatile("global_store_dwordx4 %0, %1, %2 sc0 nt" ::"v"(voff), "v"(q), "s"(sbase) : "memory");
+#ifndef LAGKV_STORE_AT_FLAGS
+#define LAGKV_STORE_AT_FLAGS "sc0 nt"
+#endif
+  asm volatile("global_store_dwordx4 %0, %1, %2 " LAGKV_STORE_AT_FLAGS ::"v"(voff), "v"(q), "s"(sbase) : "memory");
 }
 __device__ __forceinline__ void st4_out_at(void* sbase, uint32_t voff, uint32_t v) {
   asm volatile("global_store_dword %0, %1, %2" ::"v"(voff), "v"(v), "s"(sbase) : "memory");

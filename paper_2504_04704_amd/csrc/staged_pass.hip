@@ -17,8 +17,8 @@ __device__ __forceinline__ float load_elem(const char* row, int c, int ekind) {
 }
 
 // One workgroup per (stream, scored chunk).  LDS: mn/iv of K and V [4][D], spreads
-// [2][L].  Phase 1: per-channel min/max of the NEXT chunk (Eq. 7-8), one thread per
-// channel.  Phase 2: one wavefront per token: normalise (Eq. 9), mean and centred sum
+// [2][L], partial min/max [4][256].  Phase 1: per-channel min/max of the NEXT chunk
+// (Eq. 7-8), all threads (row groups x channels).  Phase 2: one wavefront per token: normalise (Eq. 9), mean and centred sum
 // of squares over the channels (Eq. 10).  Phase 3: chunk softmax and K+V sum
 // (Eq. 10-11) by wavefront 0.
 __global__ void __launch_bounds__(256) staged_score_kernel(const PassArgs a, int64_t row0,
@@ -56,22 +56,47 @@ __global__ void __launch_bounds__(256) staged_score_kernel(const PassArgs a, int
   const char* kref = kin + ref_off;
   const char* vref = vin + ref_off;
 
-  for (int c = tid; c < D; c += blockDim.x) {
-    float lo = INFINITY, hi = -INFINITY, lov = INFINITY, hiv = -INFINITY;
-    for (int r = 0; r < L; ++r) {
-      const float x = load_elem(kref + (int64_t)r * a.st, c, esize);
-      const float y = load_elem(vref + (int64_t)r * a.st, c, esize);
-      lo = fminf(lo, x);
-      hi = fmaxf(hi, x);
-      lov = fminf(lov, y);
-      hiv = fmaxf(hiv, y);
+  // Phase 1 with every thread at work: the threads form G row groups of Dc channels; group g
+  // folds rows g, g+G, ... of the reference chunk, and the G partial results per channel are
+  // combined through LDS.
+  const int nthr = blockDim.x;
+  const int Dc = D < nthr ? D : nthr, G = nthr / Dc;
+  float* red = sV + L;                       // [4][G][Dc]
+  for (int c0 = 0; c0 < D; c0 += Dc) {
+    const int g = tid / Dc, c = c0 + tid % Dc;
+    if (g < G && c < D) {
+      float lo = INFINITY, hi = -INFINITY, lov = INFINITY, hiv = -INFINITY;
+      for (int r = g; r < L; r += G) {
+        const float x = load_elem(kref + (int64_t)r * a.st, c, esize);
+        const float y = load_elem(vref + (int64_t)r * a.st, c, esize);
+        lo = fminf(lo, x);
+        hi = fmaxf(hi, x);
+        lov = fminf(lov, y);
+        hiv = fmaxf(hiv, y);
+      }
+      float* w = red + g * Dc + (c - c0);
+      w[0] = lo;
+      w[G * Dc] = hi;
+      w[2 * G * Dc] = lov;
+      w[3 * G * Dc] = hiv;
     }
-    mnK[c] = lo;
-    ivK[c] = inv_range(lo, hi);
-    mnV[c] = lov;
-    ivV[c] = inv_range(lov, hiv);
+    __syncthreads();
+    if (tid < Dc && c0 + tid < D) {
+      float lo = INFINITY, hi = -INFINITY, lov = INFINITY, hiv = -INFINITY;
+      for (int g2 = 0; g2 < G; ++g2) {
+        const float* rd = red + g2 * Dc + tid;
+        lo = fminf(lo, rd[0]);
+        hi = fmaxf(hi, rd[G * Dc]);
+        lov = fminf(lov, rd[2 * G * Dc]);
+        hiv = fmaxf(hiv, rd[3 * G * Dc]);
+      }
+      mnK[c0 + tid] = lo;
+      ivK[c0 + tid] = inv_range(lo, hi);
+      mnV[c0 + tid] = lov;
+      ivV[c0 + tid] = inv_range(lov, hiv);
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   const float inv_D = 1.0f / (float)D, inv_dof = 1.0f / (float)(D - a.ddof);
   for (int r = wave; r < L; r += nw) {
@@ -177,7 +202,8 @@ __global__ void __launch_bounds__(256) iota_rows_kernel(int32_t* __restrict__ po
 }
 
 // ------------------------------------------------------------------------ host side
-size_t staged_score_lds_bytes(int D, int L) { return ((size_t)4 * D + 2 * (size_t)L) * 4; }
+// mn/iv of K and V [4][D], variances [2][L], partial min/max of the row groups [4][256]
+size_t staged_score_lds_bytes(int D, int L) { return ((size_t)4 * D + 2 * (size_t)L + 4 * 256) * 4; }
 
 hipError_t launch_staged_score(const PassArgs& a, int64_t row0, float* scores, hipStream_t s) {
   const int64_t nblocks = (int64_t)a.B * a.H * a.n_s;

@@ -29,15 +29,22 @@ def test_algorithmic_bytes_of_the_headline_workload():
 
 
 def test_recorded_traffic_is_read_from_the_profile_summary():
-    t = bench.read_traffic("split_pass_cfg4_llama8b_128k_b4_traffic.txt")
-    assert t is not None and 86439362560 <= t < 2 * 86439362560      # at least the algorithmic bytes
+    for name in ("split_pass_cfg4_llama8b_128k_b4_traffic.txt", "hold_pass_cfg4_llama8b_128k_b4_traffic.txt"):
+        t = bench.read_traffic(name)
+        assert t is not None and 86439362560 <= t < 2 * 86439362560      # at least the algorithmic bytes
     assert bench.read_traffic("no_such_file.txt") is None
+
+
+def test_decode_algorithmic_bytes():
+    """Config 5, per call: (128 + 112 + 128) rows read, (32 + 128 + 112) written, 512 B of K+V each,
+    8192 streams."""
+    assert bench.decode_algorithmic_bytes(8192, 128, 112, 32, 128, 2) == 8192 * 640 * 512 == 2684354560
 
 
 @pytest.mark.gpu
 def test_bench_line_has_the_contract_fields():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--config", "cfg2_llama8b_16k",
-                        "--steps", "3", "--warmup", "1", "--cpu-streams", "4"],
+                        "--steps", "3", "--warmup", "1", "--cpu-streams", "4", "--only-headline"],
                        capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
@@ -54,3 +61,31 @@ def test_bench_line_has_the_contract_fields():
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     assert d["value"] > 100 * cpu["value"]
+    for key in ("kernel_ms_median", "kernel_ms_p10", "kernel_ms_p90", "frac_median", "frac_first_alloc",
+                "frac_median_of_trials", "frac_of_copy", "copy_gbs", "algorithmic_bytes"):
+        assert key in roof, key
+    assert roof["kernel_ms_p10"] <= roof["kernel_ms_median"] <= roof["kernel_ms_p90"]
+    assert d["dtype"] == "f32" and d["config"]["kv_dtype"] == "bf16" and d["config"]["compute_dtype"] == "f32"
+
+
+@pytest.mark.gpu
+def test_default_bench_run_reports_every_workload():
+    """The command the harness runs (defaults; fewer steps and placements here): the headline
+    line on the 128K configuration with configurations 2, 3 and the decode step in other_workloads."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "3", "--warmup", "1",
+                        "--placements", "2", "--cpu-streams", "8"],
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["config"]["workload"] == "cfg4_llama8b_128k_b4" and d["metric"] == "kv_tokens_compressed_per_sec_128k_ctx"
+    assert d["roofline"]["algorithmic_bytes"] == 86439362560 and len(d["config"]["placement_trials_ms"]) == 2
+    others = {o["workload"]: o for o in d["config"]["other_workloads"]}
+    assert set(others) == {"cfg2_llama8b_16k", "cfg3_llama8b_64k", "cfg5_decode_b32"}
+    for o in others.values():
+        assert 0 < o["frac"] < 1 and o["ms_p10"] <= o["ms"] <= o["ms_p90"] and o["algorithmic_bytes"] > 0
+        assert o["cpu_baseline"]["kind"] == "oracle" and o["cpu_baseline"]["value"] > 0
+    dec = others["cfg5_decode_b32"]
+    assert dec["steps"] == 64 and dec["length_after_the_first_steps"] == 8384 + 66 * 32
+    assert dec["latency_ms_p50"] <= dec["latency_ms_p99"] and dec["algorithmic_bytes"] == 2684354560

@@ -428,6 +428,96 @@ def test_prefill_chunk_by_chunk_equals_one_shot(dtype):
     oracle_history_check(cache, Kh, Vh, S, L, r)
 
 
+def _prefill_at_scale(cfg, layers, n_sample):
+    """Chunk-by-chunk prefill (S + 2L rows, then one lag per lagkv_append_and_compress call) of
+    `layers` layers of a workload configuration: the final cache against the one-shot oracle on
+    sampled streams, against the one-shot pass on all of them, and both timings."""
+    import time
+    sub = cfg.scaled(layers=layers)
+    K, V = synth.make_kv(sub, device=DEV)
+    pl = lagkv.plan(lagkv.params_for(K, cfg.S, cfg.L, cfg.r), cfg.T)
+    cache = lagkv.Cache(K.shape[0], cfg.H, cfg.D, pl.T_out + 2 * cfg.L, cfg.S, cfg.L, cfg.r)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    calls = cache.prefill_chunked(K, V)
+    torch.cuda.synchronize()
+    t_chunked = time.perf_counter() - t0
+    assert calls == 1 + -(-(cfg.T - cfg.S - 2 * cfg.L) // cfg.L)
+    assert cache.length == pl.T_out and cache.n_seen == cfg.T
+    one = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    one = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r)
+    torch.cuda.synchronize()
+    t_one = time.perf_counter() - t0
+    gK, gV, gpos = cache.view()
+    PU.check_index_invariants(gpos, cfg.T, cfg.S, cfg.L, pl.k, pl.n_scored)
+    same = (gpos == one.idx).all(dim=-1)
+    say(f"prefill chunk by chunk, {sub.streams} streams of {cfg.name}: {calls} calls in {t_chunked * 1e3:.1f} ms "
+        f"({cfg.B * cfg.T / t_chunked:.3g} tokens/s per {layers} layers); one-shot pass {t_one * 1e3:.2f} ms; "
+        f"{int(same.sum())} of {same.numel()} streams identical to the one-shot pass")
+
+    def check(s):
+        b, h = divmod(s, cfg.H)
+        return PU.check_stream(K[b, h], V[b, h], cfg.S, cfg.L, cfg.r, gpos[b, h], gK[b, h], gV[b, h])
+
+    rep = PU.StreamReport()
+    with ThreadPoolExecutor(8) as ex:
+        for r in ex.map(check, synth.stream_sample(sub.streams, n_sample)):
+            rep.merge(r)
+    # the recursion and the one-shot pass may differ only where the oracle sees a near-tie
+    assert int((~same).sum()) <= max(2, same.numel() // 16)
+    return rep
+
+
+def test_prefill_chunk_by_chunk_at_config2_scale():
+    """All 32 layers of the 16K configuration (256 streams, L = 128): 1 + 126 calls, each the
+    single-round decode kernel."""
+    rep = _prefill_at_scale(synth.CONFIGS["cfg2_llama8b_16k"], 32, 32)
+    assert rep.chunks == 32 * 126
+
+
+def test_prefill_chunk_by_chunk_on_one_layer_of_config4():
+    """One layer of the 128K configuration (B=4 x 8 heads = 32 streams, L = 512): 1 + 254 calls
+    through the general append kernel (a 512-row reference chunk does not fit the LDS of the
+    single-round kernel)."""
+    rep = _prefill_at_scale(synth.CONFIGS["cfg4_llama8b_128k_b4"], 1, 8)
+    assert rep.chunks == 8 * 254
+
+
+GRID_K = {(128, 0.5): 64, (128, 0.25): 32, (128, 0.167): 21, (128, 0.125): 16,
+          (512, 0.5): 256, (512, 0.25): 128, (512, 0.167): 85, (512, 0.125): 64,
+          (1024, 0.5): 512, (1024, 0.25): 256, (1024, 0.167): 171, (1024, 0.125): 128}
+
+
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
+@pytest.mark.parametrize("L,r", sorted(GRID_K))
+def test_paper_parameter_grid_on_qwen_shaped_streams(L, r, variant):
+    """The settings of the Experiments and Ablation sections: S = 16, L in {128, 512, 1024},
+    r in {1/2, 1/4, 0.167, 1/8} (floor(r L) kept per chunk), on a stream set shaped like
+    Qwen2.5-7B's cache (28 layers x 4 KV heads, D = 128, bf16), every scoring variant.  Index
+    invariants on all 112 streams, 10 sampled streams against the oracle."""
+    S, n_chunks = 16, 5
+    T = S + n_chunks * L + 77
+    say("grid", L, r, "variant", variant)
+    K, V = gen(28, 4, T, 128, torch.bfloat16, seed=L + int(r * 1000))
+    out = lagkv.compress(K, V, S, L, r, variant=variant, want_scores=True)
+    torch.cuda.synchronize()
+    assert out.plan.k == GRID_K[(L, r)] and out.plan.n_scored == n_chunks - 1
+    PU.check_index_invariants(out.idx, T, S, L, out.plan.k, out.plan.n_scored)
+
+    def check(s):
+        b, h = divmod(s, 4)
+        return PU.check_stream(K[b, h], V[b, h], S, L, r, out.idx[b, h], out.K[b, h], out.V[b, h],
+                               out.scores[b, h], 1, VARIANT_NAME[variant])
+
+    rep = PU.StreamReport()
+    with ThreadPoolExecutor(8) as ex:
+        for x in ex.map(check, synth.stream_sample(112, 10)):
+            rep.merge(x)
+    assert rep.chunks == 10 * (n_chunks - 1)
+
+
 def test_append_capacity_error_leaves_cache_untouched():
     cache = lagkv.Cache(1, 1, 128, 64, 4, 16, 0.5)
     Kn, Vn = gen(1, 1, 65, 128, torch.bfloat16, seed=81)
@@ -474,9 +564,46 @@ def test_config3_llama8b_64k():
 
 def test_config4_llama8b_128k_b4_bench_configuration():
     """The headline workload in the launch configuration bench.py times (defaults,
-    no score dump): 64 GiB scanned, sampled streams against the oracle."""
-    out, _ = _full_config("cfg4_llama8b_128k_b4", 128, want_scores=False)
-    assert out.plan.T_out == 33536
+    no score dump): 64 GiB scanned, 128 sampled streams against the oracle.  A second launch
+    of the same configuration with the score dump on must reproduce the first one's output, and
+    its scores are compared with the oracle on the same sample; so are the streaming kernel's
+    (the other one-shot kernel that serves this shape)."""
+    cfg = synth.CONFIGS["cfg4_llama8b_128k_b4"]
+    say("full config", cfg.name, "streams", cfg.streams, "T", cfg.T)
+    K, V = synth.make_kv(cfg, device=DEV)
+    out = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r)
+    torch.cuda.synchronize()
+    pl = out.plan
+    assert pl.T_out == 33536
+    PU.check_index_invariants(out.idx, cfg.T, cfg.S, cfg.L, pl.k, pl.n_scored)
+    scores = torch.empty((K.shape[0], cfg.H, pl.n_scored * cfg.L), dtype=torch.float32, device=DEV)
+    again = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, scores_out=scores)
+    torch.cuda.synchronize()
+    assert torch.equal(again.idx, out.idx) and torch.equal(again.K, out.K) and torch.equal(again.V, out.V)
+    del again
+    sample = synth.stream_sample(cfg.streams, 128)
+    rep = PU.StreamReport()
+
+    def one(s):
+        b, h = divmod(s, cfg.H)
+        return PU.check_stream(K[b, h], V[b, h], cfg.S, cfg.L, cfg.r, out.idx[b, h], out.K[b, h], out.V[b, h],
+                               scores[b, h])
+
+    with ThreadPoolExecutor(8) as ex:
+        for r in ex.map(one, sample):
+            rep.merge(r)
+    say(cfg.name, "ok: sampled chunks", rep.chunks, "near-tie flips", rep.flipped_chunks,
+        "max score rel err", f"{rep.max_score_rel:.2e}")
+    assert rep.chunks == 128 * 254
+    # the streaming kernel on the same workload: index invariants everywhere, scores on a few streams
+    del out
+    fused = lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, scores_out=scores, launch=hint(lagkv.PATH_FUSED))
+    torch.cuda.synchronize()
+    PU.check_index_invariants(fused.idx, cfg.T, cfg.S, cfg.L, pl.k, pl.n_scored)
+    for s in sample[:16]:
+        b, h = divmod(s, cfg.H)
+        PU.check_stream(K[b, h], V[b, h], cfg.S, cfg.L, cfg.r, fused.idx[b, h], fused.K[b, h], fused.V[b, h],
+                        scores[b, h])
 
 
 def test_config5_decode_rounds_reduced_batch():
@@ -500,9 +627,17 @@ def test_config5_decode_rounds_reduced_batch():
     Kh, Vh = torch.cat(hist_k, dim=2), torch.cat(hist_v, dim=2)
     gK, gV, gpos = cache.view()
     PU.check_index_invariants(gpos, Kh.shape[2], cfg.S, cfg.L, 32, 254 + rounds)
-    for s in synth.stream_sample(cfg.streams, 16):
+
+    def one(s):
         b, h = divmod(s, cfg.H)
-        PU.check_stream(Kh[b, h], Vh[b, h], cfg.S, cfg.L, cfg.r, gpos[b, h], gK[b, h], gV[b, h])
+        return PU.check_stream(Kh[b, h], Vh[b, h], cfg.S, cfg.L, cfg.r, gpos[b, h], gK[b, h], gV[b, h])
+
+    rep = PU.StreamReport()
+    with ThreadPoolExecutor(8) as ex:               # every one of the 256 streams
+        for r in ex.map(one, range(cfg.streams)):
+            rep.merge(r)
+    assert rep.chunks == cfg.streams * (254 + rounds)
+    say("config 5 (B=1) ok: chunks", rep.chunks, "near-tie flips", rep.flipped_chunks)
 
 
 # ------------------------------------------------------------------ HIP graph capture
@@ -544,18 +679,18 @@ def test_compress_can_be_captured_in_a_graph_and_replayed(L):
 
 
 def test_config5_decode_full_batch_sampled_streams():
-    """Config 5 at its real size (B = 32: 8192 streams, the launch bench.py --workload decode
-    times), 16 of the 64 rounds: the compressed starting cache is built layer by layer (the
-    uncompressed one would be 128 GiB), the history of a sample of streams is kept on the host,
-    and their final caches are compared with the one-shot oracle on that history."""
+    """Config 5 at its real size (B = 32: 8192 streams, the launch bench.py times), all 64
+    rounds: the compressed starting cache is built layer by layer (the uncompressed one would be
+    128 GiB), the history of 64 sampled streams is kept on the host, and their final caches are
+    compared with the one-shot oracle on that history."""
     cfg = synth.CONFIGS["cfg5_decode_b32"]
-    rounds = 16
+    rounds = 64
     say("config 5 full batch", cfg.streams, "streams")
     pl = lagkv.plan(lagkv.make_params(cfg.layers * cfg.B, cfg.H, cfg.D, cfg.S, cfg.L, cfg.r), cfg.T)
     assert pl.T_out == 8384
     cap = pl.T_out + rounds * pl.k + cfg.L
     cache = lagkv.Cache(cfg.layers * cfg.B, cfg.H, cfg.D, cap, cfg.S, cfg.L, cfg.r, track_positions=True)
-    sample = synth.stream_sample(cfg.streams, 12)
+    sample = synth.stream_sample(cfg.streams, 64)
     hist = {s: ([], []) for s in sample}
     Kl = torch.empty((cfg.B, cfg.H, cfg.T, cfg.D), dtype=torch.bfloat16, device=DEV)
     Vl = torch.empty_like(Kl)
@@ -585,8 +720,16 @@ def test_config5_decode_full_batch_sampled_streams():
     gK, gV, gpos = cache.view()
     T_hist = cfg.T + rounds * cfg.L
     PU.check_index_invariants(gpos, T_hist, cfg.S, cfg.L, 32, 254 + rounds)
-    for s in sample:
+
+    def one(s):
         bb, h = divmod(s, cfg.H)
         Kh, Vh = torch.cat(hist[s][0], dim=0), torch.cat(hist[s][1], dim=0)
         assert Kh.shape[0] == T_hist
-        PU.check_stream(Kh, Vh, cfg.S, cfg.L, cfg.r, gpos[bb, h], gK[bb, h], gV[bb, h])
+        return PU.check_stream(Kh, Vh, cfg.S, cfg.L, cfg.r, gpos[bb, h], gK[bb, h], gV[bb, h])
+
+    rep = PU.StreamReport()
+    with ThreadPoolExecutor(8) as ex:
+        for r in ex.map(one, sample):
+            rep.merge(r)
+    assert rep.chunks == 64 * (254 + rounds)
+    say("config 5 full batch ok: chunks", rep.chunks, "near-tie flips", rep.flipped_chunks)
