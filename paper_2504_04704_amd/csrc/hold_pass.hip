@@ -255,12 +255,23 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     const int next_nsb = (int)(pb - next_pb) * NSC;     // 0: this is the last batch of the segment
     const char* next_rows = tin + (S + next_pb * L) * a.st;
     if constexpr (single) folded(q ^ 1, 0, ref);
+    float vmax = 0.f;  // largest variance this wavefront has computed in this batch
+    // (every lane of a row holds the row's variance: the four rows through scalar registers)
+    auto post_vmax = [&]() __attribute__((always_inline)) {
+      const float m = fmaxf(fmaxf(rl_f(vmax, 0), rl_f(vmax, 16)), fmaxf(rl_f(vmax, 32), rl_f(vmax, 48)));
+      if (lane == 0) reinterpret_cast<float*>(selbuf)[kGroupSelPremax + wave] = m;
+    };
 
     // 1. sweep (unrolled over the pairs of steps; s is a compile-time constant)
     static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
       constexpr int s = decltype(step_tag)::value;
       constexpr int c = s / NSC;
       if constexpr (s % NSC == 0) acc.reset();
+      // The two wavefronts of a SIMD (w and w + G) compete for its issue slots and the
+      // older one wins every tie, which lets it finish its sweep a quarter earlier and then
+      // wait at the barrier.  Giving the younger one the higher priority on every other
+      // pair of steps evens the two out.
+      if (wave >= G) __builtin_amdgcn_s_setprio((s / 2) % 2 == 0 ? 1 : 0);
       if (gather && s < prev_nsb) store_prev(s, c);
       if (s < nsb) {
         // Steps s and s+1 have landed once at most NR-2 younger loads are pending (the stores
@@ -295,6 +306,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         if constexpr (single) {
           const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
           const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          vmax = fmaxf(fmaxf(vmax, v0), v1);
           if (cl == 0) {
             myvar[s * R + row0] = v0;
             myvar[(s + 1) * R + row0] = v1;
@@ -306,6 +318,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         if (c < cb) park(c);
       }
     });
+    if constexpr (single) post_vmax();
     lds_barrier();
     // 2. variances of every chunk against its reference
     if constexpr (!single) {
@@ -328,6 +341,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
             unpack<ET>(t1, x1);
             const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
             const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+            vmax = fmaxf(fmaxf(vmax, v0), v1);
             if (cl == 0) {
               myvar[s * R + row0] = v0;
               myvar[(s + 1) * R + row0] = v1;
@@ -336,12 +350,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
           }
         }
       }
+      if constexpr (C == 1) post_vmax();
       lds_barrier();
     }
     // 3. scores and selection
     if constexpr (C == 1) {
-      group_score_select(vK, vV, L, k, gather, sout ? sout + pb * L : nullptr, selbuf, list, slotmap, tid,
-                         nthreads);
+      group_score_select<true>(vK, vV, L, k, gather, sout ? sout + pb * L : nullptr, selbuf, list, slotmap, tid,
+                               nthreads);
     } else {
       if (wave < cb)
         wave_score_select<E>(vK + wave * L, vV + wave * L, L, k, gather, sout ? sout + (pb + wave) * L : nullptr,

@@ -25,6 +25,10 @@ __device__ __forceinline__ float std_of_var(float v) {
 #endif
 }
 
+// Reciprocal of a softmax denominator: the hardware reciprocal (1 ulp), as for the channel
+// ranges; the full division sequence is a dozen instructions longer.
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+
 // ---- DPP moves inside a row of 16 lanes ------------------------------------------
 // quad_perm(1,0,3,2)=0xB1 (xor 1), quad_perm(2,3,0,1)=0x4E (xor 2),
 // row_half_mirror=0x141 (i <-> 7-i), row_mirror=0x140 (i <-> 15-i).
