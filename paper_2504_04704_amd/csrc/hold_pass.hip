@@ -16,13 +16,15 @@
 //   * the stores of a batch's kept rows are deferred into the next batch's sweep: slice s
 //     of the old batch is stored right before slice s of the new batch replaces it.
 // Per batch:
-//   1. sweep: per slice, store the previous batch's slice if kept, take the new slice from
-//      the ring, fold it into the per-channel min/max of its chunk (Eq. 7-8); park the
-//      wavefront's partial result in LDS.  A batch of ONE chunk whose reference is the
-//      previous batch's chunk computes the token variances (Eq. 9-10) in the same sweep;
+//   1. sweep, the batch's chunks from the LAST one down to the first (the order of the whole
+//      walk): per slice, store the previous batch's slice if kept, take the new slice from
+//      the ring, fold it into the per-channel min/max of its chunk (Eq. 7-8) and - the
+//      reference of a chunk being the chunk swept just before it - compute the token's
+//      variance (Eq. 9-10) right away.  At the end of a chunk the wavefront parks its
+//      partial statistics in LDS, and a barrier lets the next chunk fold them;
 //                                                                        -- barrier --
-//   2. otherwise, per chunk, take the reference statistics (the next chunk's, Eq. 7-8, or
-//      the chunk's own, Eq. 14-15) and compute the variances from the registers;
+//   2. only for Eq. 14-15, where a chunk is its own reference: a second sweep over the
+//      registers computes the variances once the chunk's statistics are complete;
 //                                                                        -- barrier --
 //   3. chunk softmax, K+V sum and top-k (Eq. 10-11): all wavefronts together for a
 //      512-row chunk, one wavefront per chunk otherwise; original positions are written.
@@ -40,14 +42,18 @@ namespace lagkv {
 constexpr int kHoldSteps = 32;   // row slices a lane keeps per batch
 constexpr int kHoldWaves = 8;
 
-// Ring slots (1 KiB steps) per wavefront; divides kHoldSteps so that a step's slot is static.
-__host__ __device__ constexpr int hold_ring(int C) { return C == 1 ? 16 : 8; }
+// Ring slots (1 KiB steps) per wavefront; divides the steps of a chunk, so that a chunk
+// starts at slot 0 wherever a (short) batch starts.
+__host__ __device__ constexpr int hold_ring(int C) { return C <= 2 ? 16 : 8; }
+// Parked statistics: one slot per chunk of a batch for Eq. 14-15 (read after the sweep), two
+// that alternate from chunk to chunk for Eq. 7-8 (a chunk reads the one before it).
+__host__ __device__ constexpr int hold_stat_slots(int C, bool local) { return local ? C : 2; }
 
 struct HoldLds {
   int off_vK, off_vV, off_slot, off_list, off_sel, off_stat, off_ring, total;  // bytes
 };
 // rows: rows per batch; C: chunks per batch
-__host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C) {
+__host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C, bool local) {
   HoldLds l;
   const int kp = (k + 3) & ~3;
   l.off_vK = 0;
@@ -55,8 +61,8 @@ __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C) {
   l.off_slot = 2 * rows * 4;                 // int32 [rows]: output slot within the chunk, or -1
   l.off_list = 3 * rows * 4;                 // uint32 [C][kp]
   l.off_sel = l.off_list + C * kp * 4;
-  l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;   // float [2][C][wave][mn|mx][D]
-  l.off_ring = (l.off_stat + 2 * C * kHoldWaves * 2 * D * 4 + 1023) & ~1023;
+  l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;   // float [slot][wave][mn|mx][D]
+  l.off_ring = (l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4 + 1023) & ~1023;
   l.total = l.off_ring + kHoldWaves * hold_ring(C) * 1024;
   return l;
 }
@@ -100,9 +106,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   constexpr int L = NSC * R;
   constexpr int E = (L + kWave - 1) / kWave;
   constexpr int NR = hold_ring(C);
-  // one chunk per batch whose reference is the previous batch's chunk: a single sweep
-  constexpr bool single = C == 1 && !LOCAL;
   constexpr bool local = LOCAL;
+  static_assert(NSC % NR == 0, "a chunk starts at ring slot 0");
   extern __shared__ float4 lds_raw[];
   char* lds = reinterpret_cast<char*>(lds_raw);
   const int tid = threadIdx.x, nthreads = blockDim.x;
@@ -110,7 +115,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int k = a.k, S = a.S;
   const int kp = (k + 3) & ~3;
-  const HoldLds lay = hold_lds(a.D, kHoldSteps * R, k, C);
+  const HoldLds lay = hold_lds(a.D, kHoldSteps * R, k, C, LOCAL);
   float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
   float* vV = reinterpret_cast<float*>(lds + lay.off_vV);
   int32_t* slotmap = reinterpret_cast<int32_t*>(lds + lay.off_slot);
@@ -167,13 +172,14 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   uint4 hold[kHoldSteps];
   TStats<VEC> acc;
   TRef<VEC> ref;
-  // The partial statistics are double-buffered by batch parity: slot (q, c) holds chunk c of
-  // the batches with parity q, so that chunk 0 of the previous batch - the reference of
-  // this batch's top chunk - is still there while this batch parks its own.
-  int q = 0;
+  // Eq. 7-8: the two statistics slots alternate; `qc` is the slot that holds the statistics
+  // of the chunk swept last, the reference of the next one.  (A wavefront parks into the
+  // other slot only after it has read this one, and nobody reads that other slot again
+  // before the barrier that follows the park.)
+  int qc = 0;
 
-  // reduce acc over the row groups of the wavefront and park it as chunk c's partial result
-  auto park = [&](int c) __attribute__((always_inline)) {
+  // reduce acc over the row groups of the wavefront and park it in statistics slot `slot`
+  auto park = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int m = LPR; m < kWave; m <<= 1) {
 #pragma unroll
@@ -183,7 +189,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       }
     }
     if (rl == 0) {
-      float* w = statbuf + ((size_t)(q * C + c) * kHoldWaves + wave) * 2 * a.D + cl * VEC;
+      float* w = statbuf + ((size_t)slot * kHoldWaves + wave) * 2 * a.D + cl * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
         w[j] = acc.mn[j];
@@ -191,13 +197,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       }
     }
   };
-  // statistics of chunk c of the batch of parity qq, folded over the wavefronts of this tensor
-  auto folded = [&](int qq, int c, TRef<VEC>& out) __attribute__((always_inline)) {
+  // statistics in slot `slot`, folded over the wavefronts of this tensor
+  auto folded = [&](int slot, TRef<VEC>& out) __attribute__((always_inline)) {
     TStats<VEC> f;
     f.reset();
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float* rd = statbuf + ((size_t)(qq * C + c) * kHoldWaves + tensor * G + g) * 2 * a.D + cl * VEC;
+      const float* rd = statbuf + ((size_t)slot * kHoldWaves + tensor * G + g) * 2 * a.D + cl * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
         f.mn[j] = fminf(f.mn[j], rd[j]);
@@ -223,20 +229,25 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         acc.mx[i] = fmaxf(acc.mx[i], x[i]);
       }
     }
-    q = 1;     // parked as chunk 0 of the batch "before" the first one
-    park(0);
-    q = 0;
+    park(qc);
   }
   // Everything the compiler knows to be in flight (the copies and loads above) is drained
   // here, once; inside the loop it sees no vector-memory operation at all.
   __syncthreads();
 
+  // A batch is consumed in the order u = 0, 2, ... of "consumption indices": index u is step
+  // u % NSC of chunk C - 1 - u / NSC of the batch, i.e. step s_of(u) in position order.  A
+  // short batch (the last one of a segment) has only its lowest chunks: its first live
+  // index is kHoldSteps - nsb.  The ring slot of index u is u % NR.
   int64_t pb = p1 - C > p0 ? p1 - C : p0;
   int nsb = (int)(p1 - pb) * NSC;                       // steps of the current batch
   const char* rows = tin + (S + pb * L) * a.st;         // its first row (of this tensor)
+  {
+    const int s0 = nsb - NSC;                           // first step of its last chunk
 #pragma unroll
-  for (int s = 0; s < NR; ++s)                          // nsb >= NSC >= NR
-    dma_rows16(lane_off, rows + (int64_t)s * step_bytes, ring_base + (uint32_t)s * 1024u);
+    for (int j = 0; j < NR; ++j)
+      dma_rows16(lane_off, rows + (int64_t)(s0 + j) * step_bytes, ring_base + (uint32_t)j * 1024u);
+  }
 
   int64_t prev_pb = 0;
   int prev_nsb = 0;                                     // steps of the previous batch still to be stored
@@ -254,7 +265,6 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     const int64_t next_pb = pb - C > p0 ? pb - C : p0;
     const int next_nsb = (int)(pb - next_pb) * NSC;     // 0: this is the last batch of the segment
     const char* next_rows = tin + (S + next_pb * L) * a.st;
-    if constexpr (single) folded(q ^ 1, 0, ref);
     float vmax = 0.f;  // largest variance this wavefront has computed in this batch
     // (every lane of a row holds the row's variance: the four rows through scalar registers)
     auto post_vmax = [&]() __attribute__((always_inline)) {
@@ -262,34 +272,44 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       if (lane == 0) reinterpret_cast<float*>(selbuf)[kGroupSelPremax + wave] = m;
     };
 
-    // 1. sweep (unrolled over the pairs of steps; s is a compile-time constant)
+    // 1. sweep (unrolled over the pairs of steps; u, c and s are compile-time constants)
     static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
-      constexpr int s = decltype(step_tag)::value;
-      constexpr int c = s / NSC;
-      if constexpr (s % NSC == 0) acc.reset();
+      constexpr int u = decltype(step_tag)::value;
+      constexpr int c = C - 1 - u / NSC;
+      constexpr int s = c * NSC + u % NSC;
+      if constexpr (u % NSC == 0) {
+        acc.reset();
+        if constexpr (!local) {
+          if (c < cb) folded(qc, ref);  // the chunk swept last (by now parked by every wavefront)
+        }
+      }
       // The two wavefronts of a SIMD (w and w + G) compete for its issue slots and the
       // older one wins every tie, which lets it finish its sweep a quarter earlier and then
       // wait at the barrier.  Giving the younger one the higher priority on every other
       // pair of steps evens the two out.
-      if (wave >= G) __builtin_amdgcn_s_setprio((s / 2) % 2 == 0 ? 1 : 0);
+      if (wave >= G) __builtin_amdgcn_s_setprio((u / 2) % 2 == 0 ? 1 : 0);
       if (gather && s < prev_nsb) store_prev(s, c);
-      if (s < nsb) {
-        // Steps s and s+1 have landed once at most NR-2 younger loads are pending (the stores
-        // issued in between only make this wait stricter: operations complete in order); near
-        // the end of the segment fewer loads were issued, so everything is waited for.
+      if (c < cb) {
+        // Indices u and u+1 have landed once at most NR-2 younger loads are pending (the
+        // stores issued in between only make this wait stricter: operations complete in
+        // order); near the end of the segment fewer loads were issued, so everything is
+        // waited for.
         u32x4 qa, qb;
-        const uint32_t la = ring_lane + (uint32_t)(s % NR) * 1024u;
-        const uint32_t lb = ring_lane + (uint32_t)((s + 1) % NR) * 1024u;
-        if (s + NR <= nsb + next_nsb) lds_read_pair_after<NR - 2>(qa, qb, la, lb);
+        const uint32_t la = ring_lane + (uint32_t)(u % NR) * 1024u;
+        const uint32_t lb = ring_lane + (uint32_t)((u + 1) % NR) * 1024u;
+        if (u + NR <= kHoldSteps + next_nsb) lds_read_pair_after<NR - 2>(qa, qb, la, lb);
         else lds_read_pair_after<0>(qa, qb, la, lb);
-        // the two slots are free again: the loads NR steps ahead, into the next batch if need be
-        constexpr int t = s + NR;
-        if (t < nsb) {
-          dma_rows16(lane_off, rows + (int64_t)t * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
-          dma_rows16(lane_off, rows + (int64_t)(t + 1) * step_bytes, ring_base + (uint32_t)((t + 1) % NR) * 1024u);
-        } else if (t - nsb < next_nsb) {
-          dma_rows16(lane_off, next_rows + (int64_t)(t - nsb) * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
-          dma_rows16(lane_off, next_rows + (int64_t)(t + 1 - nsb) * step_bytes,
+        // the two slots are free again: the loads NR indices ahead, into the next batch if need be
+        constexpr int t = u + NR;
+        if constexpr (t < kHoldSteps) {
+          constexpr int st = (C - 1 - t / NSC) * NSC + t % NSC;
+          dma_rows16(lane_off, rows + (int64_t)st * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
+          dma_rows16(lane_off, rows + (int64_t)(st + 1) * step_bytes, ring_base + (uint32_t)((t + 1) % NR) * 1024u);
+        } else if (t - kHoldSteps < next_nsb) {
+          // (the next batch starts with its last chunk: steps next_nsb - NSC ...)
+          const int sn = next_nsb - NSC + (t - kHoldSteps);
+          dma_rows16(lane_off, next_rows + (int64_t)sn * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
+          dma_rows16(lane_off, next_rows + (int64_t)(sn + 1) * step_bytes,
                      ring_base + (uint32_t)((t + 1) % NR) * 1024u);
         }
         hold[s] = make_uint4(qa.x, qa.y, qa.z, qa.w);
@@ -303,7 +323,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
           acc.mx[i] = fmaxf(fmaxf(acc.mx[i], x0[i]), x1[i]);
         }
         pin(acc);
-        if constexpr (single) {
+        if constexpr (!local) {
           const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
           const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
           vmax = fmaxf(fmaxf(vmax, v0), v1);
@@ -314,20 +334,27 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         }
       }
       __builtin_amdgcn_sched_barrier(0);  // keep the pairs in order: interleaving them costs registers
-      if constexpr ((s + 2) % NSC == 0) {
-        if (c < cb) park(c);
+      if constexpr ((u + 2) % NSC == 0) {
+        if (c < cb) {
+          if constexpr (local) {
+            park(c);
+          } else {
+            park(qc ^ 1);
+            qc ^= 1;
+            // the next chunk of the batch folds these statistics at its first step
+            if constexpr (c > 0) lds_barrier();
+          }
+        }
       }
     });
-    if constexpr (single) post_vmax();
+    if constexpr (!local && C == 1) post_vmax();
     lds_barrier();
-    // 2. variances of every chunk against its reference
-    if constexpr (!single) {
+    // 2. Eq. 14-15: variances of every chunk against its own statistics
+    if constexpr (local) {
 #pragma unroll
       for (int c = 0; c < C; ++c) {
         if (c < cb) {
-          if constexpr (local) folded(q, c, ref);
-          else if (c + 1 < cb) folded(q, c + 1, ref);
-          else folded(q ^ 1, 0, ref);
+          folded(c, ref);
 #pragma unroll
           for (int j = 0; j < NSC; j += 2) {
             const int s = c * NSC + j;
@@ -377,7 +404,6 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     pb = next_pb;
     nsb = next_nsb;
     rows = next_rows;
-    q ^= 1;
   }
   static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
     constexpr int s = decltype(step_tag)::value;
@@ -401,7 +427,8 @@ bool hold_supported(int D, int esize, int L, int k) {
   const int nsc = hold_nsc(L, lpr);
   if (!nsc) return false;
   const int R = (kHoldWaves / 2) * (kWave / lpr);
-  return (size_t)hold_lds(D, kHoldSteps * R, k, kHoldSteps / nsc).total <= kHoldMaxLds;
+  // (the Eq. 14-15 layout is the larger one)
+  return (size_t)hold_lds(D, kHoldSteps * R, k, kHoldSteps / nsc, true).total <= kHoldMaxLds;
 }
 
 template <typename K>
@@ -437,7 +464,7 @@ hipError_t launch_hold_pass(const PassArgs& a, hipStream_t s) {
   if (nblocks <= 0 || nblocks > 0x7fffffffLL || a.nseg < 1 || a.nseg > a.n_s) return hipErrorInvalidValue;
   // per-lane offsets inside a step are 32 bit, and so are the step offsets of the first loads
   if (a.st * (int64_t)R * kHoldSteps >= (1LL << 31)) return hipErrorInvalidValue;
-  const size_t lds = (size_t)hold_lds(a.D, kHoldSteps * R, a.k, kHoldSteps / nsc).total;
+  const size_t lds = (size_t)hold_lds(a.D, kHoldSteps * R, a.k, kHoldSteps / nsc, a.variant == 1).total;
   const dim3 grid((unsigned)nblocks);
   if (a.esize == 4) return launch_hold_t<F32>(a, nsc, grid, lds, s);
   return a.f16 ? launch_hold_t<F16>(a, nsc, grid, lds, s) : launch_hold_t<BF16>(a, nsc, grid, lds, s);

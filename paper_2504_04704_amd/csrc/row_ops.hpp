@@ -79,6 +79,20 @@ template <int LPR, int VEC>
 __device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&mn)[VEC],
                                            const float (&iv)[VEC], float bias, float inv_D,
                                            float inv_dof) {
+#ifdef LAGKV_EXPERIMENT_ONEPASS
+  {
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      const float y = fmaf(x[j], iv[j], fmaf(-mn[j], iv[j], -0.5f));
+      s1 += y;
+      s2 = fmaf(y, y, s2);
+    }
+    s1 = group_sum<LPR>(s1);
+    s2 = group_sum<LPR>(s2);
+    return fmaf(-s1 * inv_D, s1, s2) * inv_dof;
+  }
+#endif
   float s = bias;
 #pragma unroll
   for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
