@@ -171,7 +171,11 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
 
   uint4 hold[kHoldSteps];
   TStats<VEC> acc;
-  TRef<VEC> ref;
+  // The variances are computed in one sweep over a token's channels (token_var_fast) from
+  // these statistics; where that is not accurate enough (see its bound) the whole chunk's
+  // are computed again from the rows in the registers, in two passes.
+  TRefFast<VEC> rf;
+  float vmin = 0.f, qmax = 0.f;  // smallest variance, largest sum of squares of a chunk's tokens
   // Eq. 7-8: the two statistics slots alternate; `qc` is the slot that holds the statistics
   // of the chunk swept last, the reference of the next one.  (A wavefront parks into the
   // other slot only after it has read this one, and nobody reads that other slot again
@@ -198,8 +202,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     }
   };
   // statistics in slot `slot`, folded over the wavefronts of this tensor
-  auto folded = [&](int slot, TRef<VEC>& out) __attribute__((always_inline)) {
-    TStats<VEC> f;
+  auto folded_stats = [&](int slot, TStats<VEC>& f) __attribute__((always_inline)) {
     f.reset();
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -210,6 +213,10 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         f.mx[j] = fmaxf(f.mx[j], rd[j + a.D]);
       }
     }
+  };
+  auto folded = [&](int slot, TRef<VEC>& out) __attribute__((always_inline)) {
+    TStats<VEC> f;
+    folded_stats(slot, f);
     out.from(f);
   };
 
@@ -260,6 +267,35 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     if (sl1 >= 0) st16_out_at(dst, (uint32_t)sl1 * (uint32_t)rowbytes + (uint32_t)coff, hold[s + 1]);
   };
 
+  const float guard_scale = 256.f * (float)a.D * (float)a.D;
+  // variances of this wavefront's rows of chunk c of the batch in the registers, two passes
+  // over the channels, against the statistics in slot `slot` (the rare case, see above)
+  auto redo_chunk = [&](auto c_tag, int slot, float& vmax) __attribute__((always_inline)) {
+    constexpr int c = decltype(c_tag)::value;
+    TRef<VEC> ref;
+    folded(slot, ref);
+#pragma unroll
+    for (int j = 0; j < NSC; j += 2) {
+      const int s = c * NSC + j;
+      float x0[VEC], x1[VEC];
+      // (copies made opaque to the compiler, so that it unpacks again here instead of keeping
+      // the sweep's unpacked rows alive in registers)
+      uint4 t0 = hold[s], t1 = hold[s + 1];
+      asm volatile("" : "+v"(t0.x), "+v"(t0.y), "+v"(t0.z), "+v"(t0.w));
+      asm volatile("" : "+v"(t1.x), "+v"(t1.y), "+v"(t1.z), "+v"(t1.w));
+      unpack<ET>(t0, x0);
+      unpack<ET>(t1, x1);
+      const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+      const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+      vmax = fmaxf(fmaxf(vmax, v0), v1);
+      if (cl == 0) {
+        myvar[s * R + row0] = v0;
+        myvar[(s + 1) * R + row0] = v1;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   for (int64_t pe = p1; pe > p0;) {
     const int cb = nsb / NSC;  // chunks of this batch (the last batch of a segment may be short)
     const int64_t next_pb = pb - C > p0 ? pb - C : p0;
@@ -280,7 +316,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       if constexpr (u % NSC == 0) {
         acc.reset();
         if constexpr (!local) {
-          if (c < cb) folded(qc, ref);  // the chunk swept last (by now parked by every wavefront)
+          if (c < cb) {  // reference: the chunk swept last (by now parked by every wavefront)
+            TStats<VEC> f;
+            folded_stats(qc, f);
+            rf.from(f);
+            vmin = rf.wide ? -1.f : INFINITY;
+            qmax = 0.f;
+          }
         }
       }
       // The two wavefronts of a SIMD (w and w + G) compete for its issue slots and the
@@ -292,8 +334,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       if (c < cb) {
         // Indices u and u+1 have landed once at most NR-2 younger loads are pending (the
         // stores issued in between only make this wait stricter: operations complete in
-        // order); near the end of the segment fewer loads were issued, so everything is
-        // waited for.
+        // order, and how many stores there were depends on the data); near the end of the segment fewer loads
+        // were issued, so everything is waited for.
         u32x4 qa, qb;
         const uint32_t la = ring_lane + (uint32_t)(u % NR) * 1024u;
         const uint32_t lb = ring_lane + (uint32_t)((u + 1) % NR) * 1024u;
@@ -324,9 +366,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         }
         pin(acc);
         if constexpr (!local) {
-          const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-          const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+          float q0, q1;
+          const float v0 = token_var_fast<LPR, VEC>(x0, rf.iv, rf.sh, inv_D, inv_dof, q0);
+          const float v1 = token_var_fast<LPR, VEC>(x1, rf.iv, rf.sh, inv_D, inv_dof, q1);
           vmax = fmaxf(fmaxf(vmax, v0), v1);
+          vmin = fminf(fminf(vmin, v0), v1);
+          qmax = fmaxf(fmaxf(qmax, q0), q1);
+          asm volatile("" : "+v"(vmin), "+v"(qmax), "+v"(vmax));  // evaluated here, not collected at the end
           if (cl == 0) {
             myvar[s * R + row0] = v0;
             myvar[(s + 1) * R + row0] = v1;
@@ -339,8 +385,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
           if constexpr (local) {
             park(c);
           } else {
+            const bool redo = __any(!(guard_scale * vmin >= qmax * qmax));
             park(qc ^ 1);
             qc ^= 1;
+            if (redo) {  // (after the park: the running statistics are out of the registers)
+              if constexpr (C == 1) vmax = 0.f;
+              redo_chunk(std::integral_constant<int, c>{}, qc ^ 1, vmax);
+            }
             // the next chunk of the batch folds these statistics at its first step
             if constexpr (c > 0) lds_barrier();
           }
@@ -349,12 +400,18 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     });
     if constexpr (!local && C == 1) post_vmax();
     lds_barrier();
-    // 2. Eq. 14-15: variances of every chunk against its own statistics
+    // 2. Eq. 14-15: variances of every chunk against its own statistics.  Nothing overlaps
+    // this sweep (the ring is full long before it ends), so it uses the short one-sweep
+    // variance and falls back on the two-pass form where that one is not accurate enough.
     if constexpr (local) {
-#pragma unroll
-      for (int c = 0; c < C; ++c) {
+      static_for<0, C, 1>([&](auto c_tag) __attribute__((always_inline)) {
+        constexpr int c = decltype(c_tag)::value;
         if (c < cb) {
-          folded(c, ref);
+          folded_stats(c, acc);  // (the running statistics are not in use during this sweep)
+          rf.from(acc);
+          // smallest variance and largest sum of squares of this wavefront's tokens
+          vmin = rf.wide ? -1.f : INFINITY;
+          qmax = 0.f;
 #pragma unroll
           for (int j = 0; j < NSC; j += 2) {
             const int s = c * NSC + j;
@@ -366,17 +423,27 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
             asm volatile("" : "+v"(t1.x), "+v"(t1.y), "+v"(t1.z), "+v"(t1.w));
             unpack<ET>(t0, x0);
             unpack<ET>(t1, x1);
-            const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-            const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+            float q0, q1;
+            const float v0 = token_var_fast<LPR, VEC>(x0, rf.iv, rf.sh, inv_D, inv_dof, q0);
+            const float v1 = token_var_fast<LPR, VEC>(x1, rf.iv, rf.sh, inv_D, inv_dof, q1);
             vmax = fmaxf(fmaxf(vmax, v0), v1);
+            vmin = fminf(fminf(vmin, v0), v1);
+            qmax = fmaxf(fmaxf(qmax, q0), q1);
+            asm volatile("" : "+v"(vmin), "+v"(qmax), "+v"(vmax));  // evaluated here, not collected at the end
             if (cl == 0) {
               myvar[s * R + row0] = v0;
               myvar[(s + 1) * R + row0] = v1;
             }
             __builtin_amdgcn_sched_barrier(0);
           }
+          // the rare chunk with a token outside the bound: all of this wavefront's rows again,
+          // two passes over the channels
+          if (__any(!(guard_scale * vmin >= qmax * qmax))) {
+            if constexpr (C == 1) vmax = 0.f;
+            redo_chunk(c_tag, c, vmax);
+          }
         }
-      }
+      });
       if constexpr (C == 1) post_vmax();
       lds_barrier();
     }

@@ -79,20 +79,6 @@ template <int LPR, int VEC>
 __device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&mn)[VEC],
                                            const float (&iv)[VEC], float bias, float inv_D,
                                            float inv_dof) {
-#ifdef LAGKV_EXPERIMENT_ONEPASS
-  {
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      const float y = fmaf(x[j], iv[j], fmaf(-mn[j], iv[j], -0.5f));
-      s1 += y;
-      s2 = fmaf(y, y, s2);
-    }
-    s1 = group_sum<LPR>(s1);
-    s2 = group_sum<LPR>(s2);
-    return fmaf(-s1 * inv_D, s1, s2) * inv_dof;
-  }
-#endif
   float s = bias;
 #pragma unroll
   for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
@@ -143,6 +129,53 @@ struct TRef {  // reference statistics as Eq. 9 consumes them: zbar = (x - mn) *
     }
   }
 };
+
+// Reference statistics for the one-sweep variance below: zbar - 1/2 = x * iv + sh with
+// sh = -(mn * iv) - 1/2 rounded once.
+// `wide` (the same in every lane that built it from the same statistics): some channel's
+// offset is so large against its range that the rounding of sh alone could move a score by
+// more than 2e-6 relative (|sh| > 64: the error of a token's standard deviation from this
+// source is at most 2^-25 times the r.m.s. of sh over the channels).
+template <int VEC>
+struct TRefFast {
+  float iv[VEC], sh[VEC];
+  bool wide;
+  __device__ __forceinline__ void from(const TStats<VEC>& s) {
+    float big = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      iv[j] = inv_range(s.mn[j], s.mx[j]);
+      sh[j] = fmaf(-s.mn[j], iv[j], -0.5f);
+      big = fmaxf(big, fabsf(sh[j]));
+    }
+    wide = __any(big > 64.f);
+  }
+};
+
+// Variance over the D channels of one normalised token in ONE sweep over its channels: sum
+// and sum of squares of zbar - 1/2 (normalised values lie around [0,1], so the shift keeps
+// the two sums from cancelling), 8 instructions per row slice shorter than token_var.
+// `sumsq` receives the sum of squares.  A caller must redo with token_var every token with
+// sumsq^2 > 256 * D^2 * variance (a nearly constant token: mean square^2 > 256 * variance,
+// where the subtraction of the two sums loses more than the score tolerance allows; inside
+// the bound the error of the standard deviation stays under 2e-6), and everything built on
+// `wide` statistics.
+template <int LPR, int VEC>
+__device__ __forceinline__ float token_var_fast(const float (&x)[VEC], const float (&iv)[VEC],
+                                                const float (&sh)[VEC], float inv_D, float inv_dof,
+                                                float& sumsq) {
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    const float y = fmaf(x[j], iv[j], sh[j]);
+    s1 += y;
+    s2 = fmaf(y, y, s2);
+  }
+  s1 = group_sum<LPR>(s1);
+  s2 = group_sum<LPR>(s2);
+  sumsq = s2;
+  return fmaf(-s1 * inv_D, s1, s2) * inv_dof;
+}
 
 // dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane.
 template <int LPR>

@@ -189,6 +189,38 @@ def test_register_resident_kernel_against_oracle(shape, variant):
     assert torch.equal(sc, out.scores)
 
 
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL])
+@pytest.mark.parametrize("L", [128, 256, 512])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_resident_kernel_where_the_one_sweep_variance_is_not_enough(L, dtype, variant):
+    """The register-resident kernel computes a token's variance in one sweep over its channels
+    and must fall back on the two-pass form for statistics with a huge offset against
+    their range and for tokens whose normalised values are nearly all equal."""
+    S, D = 8, (128 if dtype == torch.bfloat16 else 64)      # rows of 256 bytes
+    say("resident kernel, fallback cases", L, dtype, variant)
+    K, V = gen(1, 3, S + 5 * L + 3, D, dtype, seed=77 + L)
+    # head 0: half of the channels sit far from zero compared with their spread
+    K[0, 0, :, ::2] = K[0, 0, :, ::2] * 0.25 + 300.0
+    V[0, 0, :, 1::2] = V[0, 0, :, 1::2] * 0.25 - 200.0
+    ref_of = (lambda c: c) if variant == lagkv.SCORE_LOCAL else (lambda c: c + 1)
+    # head 1: in chunks 2 and 1 every other token equals its reference's channel minima plus
+    # a ramp that is tiny against the range (normalised values all within 1e-3 of each other)
+    for c in (2, 1):
+        lo, rlo = S + c * L, S + ref_of(c) * L
+        for T_ in (K, V):
+            mn = T_[0, 1, rlo:rlo + L].float().amin(dim=0)
+            rg = T_[0, 1, rlo:rlo + L].float().amax(dim=0) - mn
+            ramp = torch.linspace(0.5, 0.501, D, device=DEV)
+            T_[0, 1, lo + 1:lo + L:2] = (mn + rg * ramp).to(dtype)
+    # head 2: one token of chunk 0 is its reference's channel minimum everywhere (variance zero)
+    rlo = S + ref_of(0) * L
+    K[0, 2, S + 5] = K[0, 2, rlo:rlo + L].float().amin(dim=0).to(dtype)
+    V[0, 2, S + 5] = V[0, 2, rlo:rlo + L].float().amin(dim=0).to(dtype)
+    out, rep = run_and_check(K, V, S, L, 0.25, variant=variant, launch=hint(lagkv.PATH_RESIDENT))
+    assert rep.chunks == 3 * 4
+    assert torch.isfinite(out.scores).all()
+
+
 def test_register_resident_kernel_refuses_other_shapes():
     K, V = gen(1, 1, 16 + 3 * 100, 128, torch.bfloat16, seed=1)
     for kw in (dict(L=100), dict(L=128, variant=lagkv.SCORE_L2)):
