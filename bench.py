@@ -148,12 +148,11 @@ def copy_rate_gbs(src, dst, n=3):
     return 2 * cnt * src.element_size() / (s.elapsed_time(e) / n * 1e-3) / 1e9
 
 
-def kernel_name(cfg, variant: str, path: int) -> str:
-    if variant == "l2":
-        return "split_pass_kernel"
-    if path == 3 or (path == 0 and cfg.L >= 512 and cfg.D * 2 == 256):
-        return "hold_pass_kernel"
-    return "split_pass_kernel"
+def kernel_name(path: int) -> str:
+    """Name of the kernel a one-shot pass runs, from the path the library reports for it."""
+    from paper_2504_04704_amd import lagkv
+    return {lagkv.PATH_RESIDENT: "hold_pass_kernel", lagkv.PATH_FUSED: "split_pass_kernel",
+            lagkv.PATH_STAGED: "staged_score_kernel"}[path]
 
 
 def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None, cpu_streams=None,
@@ -231,7 +230,7 @@ def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None
         # Eq. 16 scores from K alone: V is read only where it is kept
         alg = cfg.streams * (K.element_size() * cfg.D * (cfg.T + 3 * pl.T_out) + 4 * pl.T_out)
     gbs = lambda ms: alg / (ms * 1e-3) / 1e9
-    kernel = kernel_name(cfg, args.variant, args.path)
+    kernel = kernel_name(lagkv.path_for(p, cfg.T))
     traffic = read_traffic(f"{kernel.replace('_kernel', '')}_{cfg.name}_traffic.txt") if args.variant == "lag" else None
     tq = quantiles(trials)
     roof = {"bound": "hbm", "achieved": gbs(q["mean"]), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -254,6 +254,16 @@ enum { LAGKV_ORDER_LINEAR = 0, LAGKV_ORDER_EVEN_ODD = 1, LAGKV_ORDER_XCD = 2, LA
 enum { LAGKV_SELECT_AUTO = 0, LAGKV_SELECT_WAVE = 1, LAGKV_SELECT_GROUP = 2 };
 int32_t lagkv_launch_hint_ex(int path, int waves, int segments, int order, int select);
 
+/*
+ * Which kernels lagkv_compress runs for these parameters (launch override included) on a
+ * cache of T rows held in 16-byte aligned buffers: LAGKV_PATH_RESIDENT, LAGKV_PATH_FUSED
+ * (the streaming one-shot kernel) or LAGKV_PATH_STAGED (the three-kernel path, which needs
+ * the workspace); for benchmarks and profiles that have to name the kernel they time.
+ * Host only.  Returns minus the lagkv_status the call itself would return for parameters
+ * it rejects.
+ */
+int lagkv_path_for(const lagkv_params* p, int64_t T);
+
 /* Static, human readable text for a lagkv_status. */
 const char* lagkv_strerror(int status);
 

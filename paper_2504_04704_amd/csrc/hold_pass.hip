@@ -50,7 +50,7 @@ __host__ __device__ constexpr int hold_ring(int C) { return C <= 2 ? 16 : 8; }
 __host__ __device__ constexpr int hold_stat_slots(int C, bool local) { return local ? C : 2; }
 
 struct HoldLds {
-  int off_vK, off_vV, off_slot, off_list, off_sel, off_stat, off_ring, total;  // bytes
+  int off_vK, off_vV, off_slot, off_list, off_sel, off_stat, off_ref, off_ring, total;  // bytes
 };
 // rows: rows per batch; C: chunks per batch
 __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C, bool local) {
@@ -62,7 +62,8 @@ __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C, bool 
   l.off_list = 3 * rows * 4;                 // uint32 [C][kp]
   l.off_sel = l.off_list + C * kp * 4;
   l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;   // float [slot][wave][mn|mx][D]
-  l.off_ring = (l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4 + 1023) & ~1023;
+  l.off_ref = l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4;  // float [K|V][iv|sh][D]
+  l.off_ring = (l.off_ref + 4 * D * 4 + 1023) & ~1023;
   l.total = l.off_ring + kHoldWaves * hold_ring(C) * 1024;
   return l;
 }
@@ -122,6 +123,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   uint32_t* list = reinterpret_cast<uint32_t*>(lds + lay.off_list);
   uint32_t* selbuf = reinterpret_cast<uint32_t*>(lds + lay.off_sel);
   float* statbuf = reinterpret_cast<float*>(lds + lay.off_stat);
+  float* refbuf = reinterpret_cast<float*>(lds + lay.off_ref);
 
   const int tensor = wave >= G ? 1 : 0;  // 0: this wavefront handles K rows, 1: V rows
   const int gslot = wave - tensor * G;
@@ -220,6 +222,30 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     out.from(f);
   };
 
+  // Eq. 7-8: the statistics every wavefront has parked in `slot` are combined and turned into
+  // the form token_var_fast takes ONCE, by one thread per channel, instead of by every lane
+  // at the start of the next chunk (which then only reads its 16 values).  To be called by
+  // all threads behind the barrier that follows the park; the result is read behind a later
+  // barrier.
+  constexpr bool shared_ref = !local;
+  auto publish_ref = [&](int slot) __attribute__((always_inline)) {
+    int t = tid;
+    asm volatile("" : "+v"(t));  // (addresses worked out here, not kept in registers across the sweep)
+    if (t < 2 * a.D) {
+      const int tn = t >= a.D ? 1 : 0, ch = t - tn * a.D;
+      float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float* rd = statbuf + ((size_t)slot * kHoldWaves + tn * G + g) * 2 * a.D + ch;
+        mn = fminf(mn, rd[0]);
+        mx = fmaxf(mx, rd[a.D]);
+      }
+      const float iv = inv_range(mn, mx);
+      refbuf[(tn * 2) * a.D + ch] = iv;
+      refbuf[(tn * 2 + 1) * a.D + ch] = fmaf(-mn, iv, -0.5f);
+    }
+  };
+
   if constexpr (!local) {
     // statistics of the chunk after the segment: the first reference
     const char* first = tin + (S + p1 * L) * a.st;
@@ -241,6 +267,10 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   // Everything the compiler knows to be in flight (the copies and loads above) is drained
   // here, once; inside the loop it sees no vector-memory operation at all.
   __syncthreads();
+  if constexpr (shared_ref) {
+    publish_ref(qc);
+    __syncthreads();
+  }
 
   // A batch is consumed in the order u = 0, 2, ... of "consumption indices": index u is step
   // u % NSC of chunk C - 1 - u / NSC of the batch, i.e. step s_of(u) in position order.  A
@@ -317,9 +347,13 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         acc.reset();
         if constexpr (!local) {
           if (c < cb) {  // reference: the chunk swept last (by now parked by every wavefront)
-            TStats<VEC> f;
-            folded_stats(qc, f);
-            rf.from(f);
+            if constexpr (shared_ref) {
+              rf.load(refbuf + (tensor * 2) * a.D + cl * VEC, refbuf + (tensor * 2 + 1) * a.D + cl * VEC);
+            } else {
+              TStats<VEC> f;
+              folded_stats(qc, f);
+              rf.from(f);
+            }
             vmin = rf.wide ? -1.f : INFINITY;
             qmax = 0.f;
           }
@@ -337,10 +371,9 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         // order, and how many stores there were depends on the data); near the end of the segment fewer loads
         // were issued, so everything is waited for.
         u32x4 qa, qb;
-        const uint32_t la = ring_lane + (uint32_t)(u % NR) * 1024u;
-        const uint32_t lb = ring_lane + (uint32_t)((u + 1) % NR) * 1024u;
-        if (u + NR <= kHoldSteps + next_nsb) lds_read_pair_after<NR - 2>(qa, qb, la, lb);
-        else lds_read_pair_after<0>(qa, qb, la, lb);
+        constexpr int oa = (u % NR) * 1024, ob = ((u + 1) % NR) * 1024;
+        if (u + NR <= kHoldSteps + next_nsb) lds_read_pair_after_at<NR - 2, oa, ob>(qa, qb, ring_lane);
+        else lds_read_pair_after_at<0, oa, ob>(qa, qb, ring_lane);
         // the two slots are free again: the loads NR indices ahead, into the next batch if need be
         constexpr int t = u + NR;
         if constexpr (t < kHoldSteps) {
@@ -392,14 +425,19 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
               if constexpr (C == 1) vmax = 0.f;
               redo_chunk(std::integral_constant<int, c>{}, qc ^ 1, vmax);
             }
-            // the next chunk of the batch folds these statistics at its first step
-            if constexpr (c > 0) lds_barrier();
+            // the next chunk of the batch takes these statistics at its first step
+            if constexpr (c > 0) {
+              lds_barrier();
+              publish_ref(qc);
+              lds_barrier();
+            }
           }
         }
       }
     });
     if constexpr (!local && C == 1) post_vmax();
     lds_barrier();
+    if constexpr (shared_ref) publish_ref(qc);  // read by the next sweep, behind the barriers of the selection
     // 2. Eq. 14-15: variances of every chunk against its own statistics.  Nothing overlaps
     // this sweep (the ring is full long before it ends), so it uses the short one-sweep
     // variance and falls back on the two-pass form where that one is not accurate enough.

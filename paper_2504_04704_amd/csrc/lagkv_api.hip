@@ -154,29 +154,28 @@ int pick_segments_split(const Norm& n, int64_t n_s, int nw) {
   return (int)nseg;
 }
 
-// Segments of the register-resident kernel: one workgroup per CU is resident, so cut the
-// streams until there are a few workgroups per CU to balance the tail; every segment reads
-// one extra chunk, so segments keep at least 16 chunks.
+// Segments of the register-resident kernel: one workgroup per CU is resident, so streams are
+// cut only until every CU has a workgroup (measured from 8 to 1024 streams: more segments
+// never pay - every segment reads one extra chunk and runs a short last batch).
 int pick_segments_hold(const Norm& n, int64_t n_s) {
   int64_t nseg = n.hint.nseg;
   if (!nseg) {
-    nseg = n.streams >= 1024 ? 1 : (1024 + n.streams - 1) / n.streams;
-    const int64_t cap = n_s / 16 > 1 ? n_s / 16 : 1;
+    nseg = n.streams >= 256 ? 1 : (256 + n.streams - 1) / n.streams;
+    const int64_t cap = n_s / 4 > 1 ? n_s / 4 : 1;
     if (nseg > cap) nseg = cap;
   }
   if (nseg > n_s) nseg = n_s;
   return (int)(nseg < 1 ? 1 : nseg);
 }
 
-// The register-resident kernel is the default where it measures faster than the streaming
-// one: chunks of 512 rows of 256 bytes, whose K+V footprint (256 KiB) the streaming kernel
-// has to read a second time from beyond the L2 for the compaction (and, for Eq. 14-15, a
-// second time for the scoring as well).  Shorter chunks stay within the L2 between their two
-// reads, and the streaming kernel's several workgroups per CU hide the per-chunk selection
-// better than the single resident one.
+// The register-resident kernel is the default wherever it applies (rows of 256 bytes, lags
+// of 128, 256 or 512 rows, Eq. 7-11 or Eq. 14-15): it reads every row once, where the
+// streaming kernel reads the kept rows a second time for the compaction (and, for
+// Eq. 14-15, every row a second time for the scoring); measured faster or equal from 8 to
+// 1024 streams.
 bool use_resident(const Norm& n) {
   if (n.variant == LAGKV_SCORE_L2 || !hold_supported(n.D, n.esize, n.L, n.k)) return false;
-  return n.hint.path == LAGKV_PATH_RESIDENT || (n.hint.path == LAGKV_PATH_AUTO && n.L >= 512);
+  return n.hint.path == LAGKV_PATH_RESIDENT || n.hint.path == LAGKV_PATH_AUTO;
 }
 
 // Launch the one-shot fused kernel.
@@ -598,6 +597,24 @@ int32_t lagkv_launch_hint_ex(int path, int waves, int segments, int order, int s
   if (base < 0 || order < 0 || order > LAGKV_ORDER_BITREV || select < 0 || select > LAGKV_SELECT_GROUP)
     return -1;
   return base | (order << kHintOrderShift) | (select << kHintSelShift);
+}
+
+int lagkv_path_for(const lagkv_params* p, int64_t T) {
+  Norm n;
+  int rc = validate(p, &n);
+  if (rc != LAGKV_OK) return -rc;
+  if (T < 1 || T > kMaxRows) return -LAGKV_ESHAPE;
+  int64_t sb, sh, st;
+  rc = strides_of(p, n, T, &sb, &sh, &st);
+  if (rc != LAGKV_OK) return -rc;
+  const int force = n.hint.path;
+  const bool fused_ok = shape_fused(n, sb, sh, st) && fused_fits(n);
+  if ((force == LAGKV_PATH_FUSED || force == LAGKV_PATH_RESIDENT) && !fused_ok) return -LAGKV_ESHAPE;
+  if (fused_ok && force != LAGKV_PATH_STAGED) {
+    if (use_resident(n)) return LAGKV_PATH_RESIDENT;
+    return force == LAGKV_PATH_RESIDENT ? -LAGKV_ESHAPE : LAGKV_PATH_FUSED;
+  }
+  return staged_fits(n) ? LAGKV_PATH_STAGED : -LAGKV_ESHAPE;
 }
 
 const char* lagkv_strerror(int status) {

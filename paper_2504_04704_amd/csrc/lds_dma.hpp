@@ -72,6 +72,20 @@ __device__ __forceinline__ void lds_read_pair_after(u32x4& a, u32x4& b, uint32_t
       : "v"(la), "v"(lb), "n"(PENDING)
       : "memory");
 }
+// The same with one base address and two immediate byte offsets (below 64 KiB): a kernel
+// whose slots are compile-time constants then keeps one address register, not one per slot.
+template <int PENDING, int OFFA, int OFFB>
+__device__ __forceinline__ void lds_read_pair_after_at(u32x4& a, u32x4& b, uint32_t base) {
+  static_assert(OFFA >= 0 && OFFA < 65536 && OFFB >= 0 && OFFB < 65536, "ds_read offset field");
+  asm volatile(
+      "s_waitcnt vmcnt(%3)\n\t"
+      "ds_read_b128 %0, %2 offset:%4\n\t"
+      "ds_read_b128 %1, %2 offset:%5\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(a), "=&v"(b)
+      : "v"(base), "n"(PENDING), "n"(OFFA), "n"(OFFB)
+      : "memory");
+}
 __device__ __forceinline__ void lds_store_f32(uint32_t addr, float v) {
   asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
 }

@@ -150,6 +150,17 @@ struct TRefFast {
     }
     wide = __any(big > 64.f);
   }
+  // the same from values computed elsewhere (VEC consecutive channels each)
+  __device__ __forceinline__ void load(const float* ivp, const float* shp) {
+    float big = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      iv[j] = ivp[j];
+      sh[j] = shp[j];
+      big = fmaxf(big, fabsf(sh[j]));
+    }
+    wide = __any(big > 64.f);
+  }
 };
 
 // Variance over the D channels of one normalised token in ONE sweep over its channels: sum

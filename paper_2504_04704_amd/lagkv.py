@@ -28,7 +28,8 @@ SELECT_AUTO, SELECT_WAVE, SELECT_GROUP = 0, 1, 2
 EXPORTS = ("lagkv_plan", "lagkv_keep_for_compression", "lagkv_workspace_bytes", "lagkv_score",
            "lagkv_select", "lagkv_compress", "lagkv_compress_static", "lagkv_cache_after_compress",
            "lagkv_prefill_rows",
-           "lagkv_append_and_compress", "lagkv_launch_hint", "lagkv_launch_hint_ex", "lagkv_strerror",
+           "lagkv_append_and_compress", "lagkv_launch_hint", "lagkv_launch_hint_ex", "lagkv_path_for",
+           "lagkv_strerror",
            "lagkv_version")
 
 
@@ -98,6 +99,8 @@ def load():
     lib.lagkv_launch_hint.restype = C.c_int32
     lib.lagkv_launch_hint_ex.argtypes = [C.c_int] * 5
     lib.lagkv_launch_hint_ex.restype = C.c_int32
+    lib.lagkv_path_for.argtypes = [C.POINTER(Params), C.c_int64]
+    lib.lagkv_path_for.restype = C.c_int
     lib.lagkv_strerror.argtypes = [C.c_int]
     lib.lagkv_strerror.restype = C.c_char_p
     lib.lagkv_version.argtypes = []
@@ -120,6 +123,14 @@ def _check(status: int, where: str):
 
 
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
+
+
+def path_for(p: "Params", T: int) -> int:
+    """lagkv_path_for: the PATH_* lagkv_compress takes for these parameters."""
+    v = load().lagkv_path_for(C.byref(p), T)
+    if v < 0:
+        raise LagKVError(-v, "lagkv_path_for")
+    return v
 
 
 def launch_hint(path: int = PATH_AUTO, waves: int = 0, segments: int = 0, order: int = 0,

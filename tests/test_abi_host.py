@@ -218,6 +218,31 @@ def test_launch_hint_is_a_pure_function(lib):
     assert lagkv.workspace_bytes(lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32), 4096) == 0
 
 
+def test_path_for_names_the_kernels_of_a_call(lib):
+    """lagkv_path_for: rows of 256 bytes with a lag of 128, 256 or 512 go to the register-resident
+    kernel (not Eq. 16), other fused shapes to the streaming kernel, the rest to the
+    three-kernel path; hints are honoured or refused as lagkv_compress does."""
+    mk = lagkv.make_params
+    T = 16 + 8 * 512
+    for L in (128, 256, 512):
+        assert lagkv.path_for(mk(2, 8, 128, 16, L, 0.25, lagkv.BF16), T) == lagkv.PATH_RESIDENT
+        assert lagkv.path_for(mk(2, 8, 64, 16, L, 0.25, lagkv.F32), T) == lagkv.PATH_RESIDENT
+        assert lagkv.path_for(mk(2, 8, 128, 16, L, 0.25, lagkv.BF16, variant=lagkv.SCORE_LOCAL), T) == lagkv.PATH_RESIDENT
+        assert lagkv.path_for(mk(2, 8, 128, 16, L, 0.25, lagkv.BF16, variant=lagkv.SCORE_L2), T) == lagkv.PATH_FUSED
+        assert lagkv.path_for(mk(2, 8, 128, 16, L, 0.25, lagkv.BF16, launch=lagkv.launch_hint(lagkv.PATH_FUSED)), T) \
+            == lagkv.PATH_FUSED
+        assert lagkv.path_for(mk(2, 8, 128, 16, L, 0.25, lagkv.BF16, launch=lagkv.launch_hint(lagkv.PATH_STAGED)), T) \
+            == lagkv.PATH_STAGED
+    assert lagkv.path_for(mk(2, 8, 128, 16, 100, 0.25, lagkv.BF16), T) == lagkv.PATH_FUSED
+    assert lagkv.path_for(mk(2, 8, 128, 16, 512, 0.25, lagkv.F32), T) == lagkv.PATH_FUSED      # rows of 512 bytes
+    assert lagkv.path_for(mk(2, 8, 40, 16, 128, 0.25, lagkv.F32), T) == lagkv.PATH_STAGED      # rows of 160 bytes
+    for bad in (mk(2, 8, 128, 16, 100, 0.25, lagkv.BF16, launch=lagkv.launch_hint(lagkv.PATH_RESIDENT)),
+                mk(2, 8, 40, 16, 128, 0.25, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))):
+        assert lib.lagkv_path_for(C.byref(bad), T) == -lagkv.ESHAPE
+    assert lib.lagkv_path_for(C.byref(mk(2, 8, 128, 16, 128, 0.001, lagkv.BF16)), T) == -lagkv.EINVAL
+    assert lib.lagkv_path_for(C.byref(mk(2, 8, 128, 16, 128, 0.25, lagkv.BF16)), 0) == -lagkv.ESHAPE
+
+
 def test_cache_after_compress_and_prefill_rows_follow_eq12(lib):
     """The host calls that keep the partition integers behind the ABI, against the oracle's plan."""
     rng = np.random.default_rng(5)
