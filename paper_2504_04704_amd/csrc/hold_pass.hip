@@ -278,20 +278,27 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   // index is kHoldSteps - nsb.  The ring slot of index u is u % NR.
   int64_t pb = p1 - C > p0 ? p1 - C : p0;
   int nsb = (int)(p1 - pb) * NSC;                       // steps of the current batch
-  const char* rows = tin + (S + pb * L) * a.st;         // its first row (of this tensor)
-  {
-    const int s0 = nsb - NSC;                           // first step of its last chunk
+  // The loads follow the consumption order with one running address: a step further after
+  // every load and, after the last step of a chunk, back to the first step of the chunk
+  // before it - which is the next one to sweep, in this batch or in the one after it.
+  const char* dma_ptr = tin + (S + pb * L) * a.st + (int64_t)(nsb - NSC) * step_bytes;
+  const int64_t chunk_back = 2 * (int64_t)NSC * step_bytes;
+  // load of the index that sits `pos` steps into its chunk (pos: compile-time) into ring slot `slot`
+  auto dma_next = [&](int pos, int slot) __attribute__((always_inline)) {
+    dma_rows16(lane_off, dma_ptr, ring_base + (uint32_t)slot * 1024u);
+    dma_ptr += step_bytes;
+    if (pos == NSC - 1) dma_ptr -= chunk_back;
+  };
 #pragma unroll
-    for (int j = 0; j < NR; ++j)
-      dma_rows16(lane_off, rows + (int64_t)(s0 + j) * step_bytes, ring_base + (uint32_t)j * 1024u);
-  }
+  for (int j = 0; j < NR; ++j) dma_next(j, j);  // (NR <= NSC: inside the batch's last chunk)
 
-  int64_t prev_pb = 0;
+  char* prev_dst = tout;                                // output of the previous batch's first chunk
+  const int64_t kbytes = (int64_t)k * rowbytes;
   int prev_nsb = 0;                                     // steps of the previous batch still to be stored
 
   // kept slices s, s+1 of the previous batch -> output (chunk c of that batch)
   auto store_prev = [&](int s, int c) __attribute__((always_inline)) {
-    char* dst = tout + (S + (prev_pb + c) * k) * rowbytes;  // wave-uniform
+    char* dst = prev_dst + (int64_t)c * kbytes;  // wave-uniform
     const int sl0 = slotmap[s * R + row0], sl1 = slotmap[(s + 1) * R + row0];
     if (sl0 >= 0) st16_out_at(dst, (uint32_t)sl0 * (uint32_t)rowbytes + (uint32_t)coff, hold[s]);
     if (sl1 >= 0) st16_out_at(dst, (uint32_t)sl1 * (uint32_t)rowbytes + (uint32_t)coff, hold[s + 1]);
@@ -330,7 +337,6 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     const int cb = nsb / NSC;  // chunks of this batch (the last batch of a segment may be short)
     const int64_t next_pb = pb - C > p0 ? pb - C : p0;
     const int next_nsb = (int)(pb - next_pb) * NSC;     // 0: this is the last batch of the segment
-    const char* next_rows = tin + (S + next_pb * L) * a.st;
     float vmax = 0.f;  // largest variance this wavefront has computed in this batch
     // (every lane of a row holds the row's variance: the four rows through scalar registers)
     auto post_vmax = [&]() __attribute__((always_inline)) {
@@ -376,16 +382,9 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         else lds_read_pair_after_at<0, oa, ob>(qa, qb, ring_lane);
         // the two slots are free again: the loads NR indices ahead, into the next batch if need be
         constexpr int t = u + NR;
-        if constexpr (t < kHoldSteps) {
-          constexpr int st = (C - 1 - t / NSC) * NSC + t % NSC;
-          dma_rows16(lane_off, rows + (int64_t)st * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
-          dma_rows16(lane_off, rows + (int64_t)(st + 1) * step_bytes, ring_base + (uint32_t)((t + 1) % NR) * 1024u);
-        } else if (t - kHoldSteps < next_nsb) {
-          // (the next batch starts with its last chunk: steps next_nsb - NSC ...)
-          const int sn = next_nsb - NSC + (t - kHoldSteps);
-          dma_rows16(lane_off, next_rows + (int64_t)sn * step_bytes, ring_base + (uint32_t)(t % NR) * 1024u);
-          dma_rows16(lane_off, next_rows + (int64_t)(sn + 1) * step_bytes,
-                     ring_base + (uint32_t)((t + 1) % NR) * 1024u);
+        if (t < kHoldSteps || t - kHoldSteps < next_nsb) {
+          dma_next(t % NSC, t % NR);
+          dma_next((t + 1) % NSC, (t + 1) % NR);
         }
         hold[s] = make_uint4(qa.x, qa.y, qa.z, qa.w);
         hold[s + 1] = make_uint4(qb.x, qb.y, qb.z, qb.w);
@@ -503,12 +502,11 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     // The kept rows stay in the registers; the next sweep (or the flush below) stores them.
     // The next batch rewrites the statistics and variances (last read before the barrier
     // above) during its sweep, the slot map and the lists only after its own first barrier.
-    prev_pb = pb;
+    prev_dst = tout + (S + pb * k) * rowbytes;
     prev_nsb = nsb;
     pe = pb;
     pb = next_pb;
     nsb = next_nsb;
-    rows = next_rows;
   }
   static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
     constexpr int s = decltype(step_tag)::value;
