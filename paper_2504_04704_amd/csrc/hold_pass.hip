@@ -62,8 +62,9 @@ __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C, bool 
   l.off_list = 3 * rows * 4;                 // uint32 [C][kp]
   l.off_sel = l.off_list + C * kp * 4;
   l.off_stat = (l.off_sel + group_sel_bytes() + 15) & ~15;   // float [slot][wave][mn|mx][D]
-  l.off_ref = l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4;  // float [K|V][iv|sh][D]
-  l.off_ring = (l.off_ref + 4 * D * 4 + 1023) & ~1023;
+  // float [chunk of the batch (Eq. 14-15) | 1][K|V][iv|sh][D]
+  l.off_ref = l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4;
+  l.off_ring = (l.off_ref + (local ? C : 1) * 4 * D * 4 + 1023) & ~1023;
   l.total = l.off_ring + kHoldWaves * hold_ring(C) * 1024;
   return l;
 }
@@ -222,13 +223,12 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     out.from(f);
   };
 
-  // Eq. 7-8: the statistics every wavefront has parked in `slot` are combined and turned into
-  // the form token_var_fast takes ONCE, by one thread per channel, instead of by every lane
-  // at the start of the next chunk (which then only reads its 16 values).  To be called by
-  // all threads behind the barrier that follows the park; the result is read behind a later
+  // The statistics every wavefront has parked in `slot` are combined and turned into the form
+  // token_var_fast takes ONCE, by one thread per channel, instead of by every lane where it
+  // needs them (which then only reads its 16 values from `out`).  To be called by all
+  // threads behind the barrier that follows the park; the result is read behind a later
   // barrier.
-  constexpr bool shared_ref = !local;
-  auto publish_ref = [&](int slot) __attribute__((always_inline)) {
+  auto publish_ref = [&](int slot, float* out) __attribute__((always_inline)) {
     int t = tid;
     asm volatile("" : "+v"(t));  // (addresses worked out here, not kept in registers across the sweep)
     if (t < 2 * a.D) {
@@ -241,8 +241,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         mx = fmaxf(mx, rd[a.D]);
       }
       const float iv = inv_range(mn, mx);
-      refbuf[(tn * 2) * a.D + ch] = iv;
-      refbuf[(tn * 2 + 1) * a.D + ch] = fmaf(-mn, iv, -0.5f);
+      out[(tn * 2) * a.D + ch] = iv;
+      out[(tn * 2 + 1) * a.D + ch] = fmaf(-mn, iv, -0.5f);
     }
   };
 
@@ -267,8 +267,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   // Everything the compiler knows to be in flight (the copies and loads above) is drained
   // here, once; inside the loop it sees no vector-memory operation at all.
   __syncthreads();
-  if constexpr (shared_ref) {
-    publish_ref(qc);
+  if constexpr (!local) {
+    publish_ref(qc, refbuf);
     __syncthreads();
   }
 
@@ -353,13 +353,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
         acc.reset();
         if constexpr (!local) {
           if (c < cb) {  // reference: the chunk swept last (by now parked by every wavefront)
-            if constexpr (shared_ref) {
-              rf.load(refbuf + (tensor * 2) * a.D + cl * VEC, refbuf + (tensor * 2 + 1) * a.D + cl * VEC);
-            } else {
-              TStats<VEC> f;
-              folded_stats(qc, f);
-              rf.from(f);
-            }
+            rf.load(refbuf + (tensor * 2) * a.D + cl * VEC, refbuf + (tensor * 2 + 1) * a.D + cl * VEC);
             vmin = rf.wide ? -1.f : INFINITY;
             qmax = 0.f;
           }
@@ -427,7 +421,7 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
             // the next chunk of the batch takes these statistics at its first step
             if constexpr (c > 0) {
               lds_barrier();
-              publish_ref(qc);
+              publish_ref(qc, refbuf);
               lds_barrier();
             }
           }
@@ -436,16 +430,20 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     });
     if constexpr (!local && C == 1) post_vmax();
     lds_barrier();
-    if constexpr (shared_ref) publish_ref(qc);  // read by the next sweep, behind the barriers of the selection
+    if constexpr (!local) publish_ref(qc, refbuf);  // read by the next sweep, behind the barriers of the selection
     // 2. Eq. 14-15: variances of every chunk against its own statistics.  Nothing overlaps
     // this sweep (the ring is full long before it ends), so it uses the short one-sweep
     // variance and falls back on the two-pass form where that one is not accurate enough.
     if constexpr (local) {
+#pragma unroll
+      for (int c = 0; c < C; ++c)
+        if (c < cb) publish_ref(c, refbuf + c * 4 * a.D);
+      lds_barrier();
       static_for<0, C, 1>([&](auto c_tag) __attribute__((always_inline)) {
         constexpr int c = decltype(c_tag)::value;
         if (c < cb) {
-          folded_stats(c, acc);  // (the running statistics are not in use during this sweep)
-          rf.from(acc);
+          const float* rb = refbuf + c * 4 * a.D;
+          rf.load(rb + (tensor * 2) * a.D + cl * VEC, rb + (tensor * 2 + 1) * a.D + cl * VEC);
           // smallest variance and largest sum of squares of this wavefront's tokens
           vmin = rf.wide ? -1.f : INFINITY;
           qmax = 0.f;
