@@ -42,9 +42,8 @@ namespace lagkv {
 constexpr int kHoldSteps = 32;   // row slices a lane keeps per batch
 constexpr int kHoldWaves = 8;
 
-// Ring slots (1 KiB steps) per wavefront; divides the steps of a chunk, so that a chunk
-// starts at slot 0 wherever a (short) batch starts.
-__host__ __device__ constexpr int hold_ring(int C) { return C <= 2 ? 16 : 8; }
+// Ring slots (1 KiB steps) per wavefront: as many as the LDS holds beside the statistics.
+__host__ __device__ constexpr int hold_ring(int C, bool local) { return local && C > 2 ? 8 : 16; }
 // Parked statistics: one slot per chunk of a batch for Eq. 14-15 (read after the sweep), two
 // that alternate from chunk to chunk for Eq. 7-8 (a chunk reads the one before it).
 __host__ __device__ constexpr int hold_stat_slots(int C, bool local) { return local ? C : 2; }
@@ -65,7 +64,7 @@ __host__ __device__ inline HoldLds hold_lds(int D, int rows, int k, int C, bool 
   // float [chunk of the batch (Eq. 14-15) | 1][K|V][iv|sh][D]
   l.off_ref = l.off_stat + hold_stat_slots(C, local) * kHoldWaves * 2 * D * 4;
   l.off_ring = (l.off_ref + (local ? C : 1) * 4 * D * 4 + 1023) & ~1023;
-  l.total = l.off_ring + kHoldWaves * hold_ring(C) * 1024;
+  l.total = l.off_ring + kHoldWaves * hold_ring(C, local) * 1024;
   return l;
 }
 
@@ -107,9 +106,9 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   constexpr int C = kHoldSteps / NSC;
   constexpr int L = NSC * R;
   constexpr int E = (L + kWave - 1) / kWave;
-  constexpr int NR = hold_ring(C);
+  constexpr int NR = hold_ring(C, LOCAL);
   constexpr bool local = LOCAL;
-  static_assert(NSC % NR == 0, "a chunk starts at ring slot 0");
+  static_assert(kHoldSteps % NR == 0 && NR % 2 == 0, "a batch starts at ring slot 0");
   extern __shared__ float4 lds_raw[];
   char* lds = reinterpret_cast<char*>(lds_raw);
   const int tid = threadIdx.x, nthreads = blockDim.x;
@@ -273,24 +272,33 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   }
 
   // A batch is consumed in the order u = 0, 2, ... of "consumption indices": index u is step
-  // u % NSC of chunk C - 1 - u / NSC of the batch, i.e. step s_of(u) in position order.  A
-  // short batch (the last one of a segment) has only its lowest chunks: its first live
-  // index is kHoldSteps - nsb.  The ring slot of index u is u % NR.
-  int64_t pb = p1 - C > p0 ? p1 - C : p0;
-  int nsb = (int)(p1 - pb) * NSC;                       // steps of the current batch
+  // u % NSC of chunk C - 1 - u / NSC of the batch, i.e. step s_of(u) in position order.  The
+  // FIRST batch of a segment takes the chunks that do not fill a batch (its lowest chunk
+  // numbers; its first live index is kHoldSteps - nsb), all later ones are full.  The ring
+  // slot of index u is u % NR.
+  int nsb = (int)((p1 - p0 - 1) % C + 1) * NSC;         // steps of the current batch
+  int64_t pb = p1 - nsb / NSC;                          // its first chunk
+  int seg_left = (int)(p1 - p0) * NSC;                  // steps of the segment not yet swept ...
+  int dma_left = seg_left;                              // ... and not yet asked for
   // The loads follow the consumption order with one running address: a step further after
   // every load and, after the last step of a chunk, back to the first step of the chunk
   // before it - which is the next one to sweep, in this batch or in the one after it.
-  const char* dma_ptr = tin + (S + pb * L) * a.st + (int64_t)(nsb - NSC) * step_bytes;
+  const char* dma_ptr = tin + (S + (p1 - 1) * L) * a.st;
   const int64_t chunk_back = 2 * (int64_t)NSC * step_bytes;
-  // load of the index that sits `pos` steps into its chunk (pos: compile-time) into ring slot `slot`
+  // load of the next index, which sits `pos` steps into its chunk, into ring slot `slot`
   auto dma_next = [&](int pos, int slot) __attribute__((always_inline)) {
-    dma_rows16(lane_off, dma_ptr, ring_base + (uint32_t)slot * 1024u);
-    dma_ptr += step_bytes;
-    if (pos == NSC - 1) dma_ptr -= chunk_back;
+    if (dma_left > 0) {
+      dma_rows16(lane_off, dma_ptr, ring_base + (uint32_t)slot * 1024u);
+      dma_ptr += step_bytes;
+      if (pos == NSC - 1) dma_ptr -= chunk_back;
+      --dma_left;
+    }
   };
+  {
+    const int u0 = kHoldSteps - nsb;
 #pragma unroll
-  for (int j = 0; j < NR; ++j) dma_next(j, j);  // (NR <= NSC: inside the batch's last chunk)
+    for (int j = 0; j < NR; ++j) dma_next(j % NSC, (u0 + j) % NR);
+  }
 
   char* prev_dst = tout;                                // output of the previous batch's first chunk
   const int64_t kbytes = (int64_t)k * rowbytes;
@@ -333,10 +341,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     }
   };
 
-  for (int64_t pe = p1; pe > p0;) {
-    const int cb = nsb / NSC;  // chunks of this batch (the last batch of a segment may be short)
-    const int64_t next_pb = pb - C > p0 ? pb - C : p0;
-    const int next_nsb = (int)(pb - next_pb) * NSC;     // 0: this is the last batch of the segment
+  while (seg_left > 0) {
+    const int cb = nsb / NSC;  // chunks of this batch (the first batch of a segment may be short)
     float vmax = 0.f;  // largest variance this wavefront has computed in this batch
     // (every lane of a row holds the row's variance: the four rows through scalar registers)
     auto post_vmax = [&]() __attribute__((always_inline)) {
@@ -368,18 +374,17 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
       if (c < cb) {
         // Indices u and u+1 have landed once at most NR-2 younger loads are pending (the
         // stores issued in between only make this wait stricter: operations complete in
-        // order, and how many stores there were depends on the data); near the end of the segment fewer loads
-        // were issued, so everything is waited for.
+        // order, and how many stores there were depends on the data); for the last steps of
+        // the segment fewer loads were issued, so everything is waited for.
         u32x4 qa, qb;
         constexpr int oa = (u % NR) * 1024, ob = ((u + 1) % NR) * 1024;
-        if (u + NR <= kHoldSteps + next_nsb) lds_read_pair_after_at<NR - 2, oa, ob>(qa, qb, ring_lane);
+        if (seg_left >= NR) lds_read_pair_after_at<NR - 2, oa, ob>(qa, qb, ring_lane);
         else lds_read_pair_after_at<0, oa, ob>(qa, qb, ring_lane);
+        seg_left -= 2;
         // the two slots are free again: the loads NR indices ahead, into the next batch if need be
         constexpr int t = u + NR;
-        if (t < kHoldSteps || t - kHoldSteps < next_nsb) {
-          dma_next(t % NSC, t % NR);
-          dma_next((t + 1) % NSC, (t + 1) % NR);
-        }
+        dma_next(t % NSC, t % NR);
+        dma_next((t + 1) % NSC, (t + 1) % NR);
         hold[s] = make_uint4(qa.x, qa.y, qa.z, qa.w);
         hold[s + 1] = make_uint4(qb.x, qb.y, qb.z, qb.w);
         float x0[VEC], x1[VEC];
@@ -502,9 +507,8 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     // above) during its sweep, the slot map and the lists only after its own first barrier.
     prev_dst = tout + (S + pb * k) * rowbytes;
     prev_nsb = nsb;
-    pe = pb;
-    pb = next_pb;
-    nsb = next_nsb;
+    pb -= C;
+    nsb = kHoldSteps;
   }
   static_for<0, kHoldSteps, 2>([&](auto step_tag) __attribute__((always_inline)) {
     constexpr int s = decltype(step_tag)::value;
@@ -528,8 +532,8 @@ bool hold_supported(int D, int esize, int L, int k) {
   const int nsc = hold_nsc(L, lpr);
   if (!nsc) return false;
   const int R = (kHoldWaves / 2) * (kWave / lpr);
-  // (the Eq. 14-15 layout is the larger one)
-  return (size_t)hold_lds(D, kHoldSteps * R, k, kHoldSteps / nsc, true).total <= kHoldMaxLds;
+  return (size_t)hold_lds(D, kHoldSteps * R, k, kHoldSteps / nsc, true).total <= kHoldMaxLds &&
+         (size_t)hold_lds(D, kHoldSteps * R, k, kHoldSteps / nsc, false).total <= kHoldMaxLds;
 }
 
 template <typename K>
