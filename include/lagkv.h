@@ -223,8 +223,10 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const v
  * arguments into the value lagkv_params.launch carries for ONE call; the library keeps
  * nothing.  0 in any argument means "choose automatically" (and launch = 0 is the same as
  * lagkv_launch_hint(0, 0, 0)).
- *   path      LAGKV_PATH_AUTO; LAGKV_PATH_FUSED (error LAGKV_ESHAPE when the fused kernels
- *             do not cover the shape); LAGKV_PATH_STAGED (three-kernel path); or
+ *   path      LAGKV_PATH_AUTO (the register-resident kernel where it applies, else the
+ *             streaming fused kernel, else the three-kernel path); LAGKV_PATH_FUSED (the
+ *             streaming fused kernel; error LAGKV_ESHAPE when the fused kernels do not
+ *             cover the shape); LAGKV_PATH_STAGED (three-kernel path); or
  *             LAGKV_PATH_RESIDENT (the one-shot kernel that keeps a batch of rows in
  *             registers and reads every row once: 256-byte rows, L of 128, 256 or 512,
  *             not Eq. 16; LAGKV_ESHAPE otherwise; append calls treat it as FUSED)

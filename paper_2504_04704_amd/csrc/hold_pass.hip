@@ -12,7 +12,7 @@
 // is kept going from inside:
 //   * rows arrive through a per-wavefront LDS ring filled by asynchronous global->LDS loads
 //     that run a fixed number of steps AHEAD of the arithmetic, across batch borders: while
-//     a batch is folded and selected, the first steps of the next batch are in flight;
+//     a batch is selected, the first steps of the next batch are in flight;
 //   * the stores of a batch's kept rows are deferred into the next batch's sweep: slice s
 //     of the old batch is stored right before slice s of the new batch replaces it.
 // Per batch:
@@ -20,8 +20,11 @@
 //      walk): per slice, store the previous batch's slice if kept, take the new slice from
 //      the ring, fold it into the per-channel min/max of its chunk (Eq. 7-8) and - the
 //      reference of a chunk being the chunk swept just before it - compute the token's
-//      variance (Eq. 9-10) right away.  At the end of a chunk the wavefront parks its
-//      partial statistics in LDS, and a barrier lets the next chunk fold them;
+//      variance (Eq. 9-10) right away, in one sweep over its channels (token_var_fast; a
+//      chunk outside that form's error bound is redone in two passes from the registers).
+//      At the end of a chunk the wavefront parks its partial statistics in LDS; behind a
+//      barrier one thread per channel combines them and publishes what the variance of the
+//      next chunk needs, which every lane then only reads;
 //                                                                        -- barrier --
 //   2. only for Eq. 14-15, where a chunk is its own reference: a second sweep over the
 //      registers computes the variances once the chunk's statistics are complete;
