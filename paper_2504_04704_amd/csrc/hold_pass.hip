@@ -187,24 +187,27 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
   // before the barrier that follows the park.)
   int qc = 0;
 
-  // reduce acc over the row groups of the wavefront and park it in statistics slot `slot`
+  // reduce acc over the four row groups of the wavefront and park it in statistics slot
+  // `slot`.  The reduction scatters: in the exchange across 16 lanes one side keeps the
+  // minima and the other the (negated) maxima, in the exchange across 32 lanes each side
+  // keeps half of the channels, so that 12 (not 32) values cross lanes and every lane ends
+  // up storing VEC/2 finished values.
   auto park = [&](int slot) __attribute__((always_inline)) {
+    constexpr int H = VEC / 2;
+    const bool hi16 = (lane & 16) != 0, hi32 = (lane & 32) != 0;
+    float keep[VEC];
 #pragma unroll
-    for (int m = LPR; m < kWave; m <<= 1) {
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) {
-        acc.mn[j] = fminf(acc.mn[j], __shfl_xor(acc.mn[j], m));
-        acc.mx[j] = fmaxf(acc.mx[j], __shfl_xor(acc.mx[j], m));
-      }
+    for (int j = 0; j < VEC; ++j) {
+      const float lo = acc.mn[j], nhi = -acc.mx[j];
+      keep[j] = fminf(hi16 ? nhi : lo, __shfl_xor(hi16 ? lo : nhi, 16));
     }
-    if (rl == 0) {
-      float* w = statbuf + ((size_t)slot * kHoldWaves + wave) * 2 * a.D + cl * VEC;
+    float fin[H];
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) {
-        w[j] = acc.mn[j];
-        w[a.D + j] = acc.mx[j];
-      }
-    }
+    for (int i = 0; i < H; ++i)
+      fin[i] = fminf(hi32 ? keep[H + i] : keep[i], __shfl_xor(hi32 ? keep[i] : keep[H + i], 32));
+    float* w = statbuf + ((size_t)slot * kHoldWaves + wave) * 2 * a.D + (hi16 ? a.D : 0) + cl * VEC + (hi32 ? H : 0);
+#pragma unroll
+    for (int i = 0; i < H; ++i) w[i] = hi16 ? -fin[i] : fin[i];
   };
   // statistics in slot `slot`, folded over the wavefronts of this tensor
   auto folded_stats = [&](int slot, TStats<VEC>& f) __attribute__((always_inline)) {
@@ -492,15 +495,16 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
     }
     // 3. scores and selection
     if constexpr (C == 1) {
+      // (the kept tokens' original positions go out from the selection itself)
       group_score_select<true>(vK, vV, L, k, gather, sout ? sout + pb * L : nullptr, selbuf, list, slotmap, tid,
-                               nthreads);
+                               nthreads, iout ? iout + S + pb * k : nullptr, (uint32_t)(S + pb * L));
     } else {
       if (wave < cb)
         wave_score_select<E>(vK + wave * L, vV + wave * L, L, k, gather, sout ? sout + (pb + wave) * L : nullptr,
                              list + wave * kp, slotmap + wave * L, lane);
     }
     lds_barrier();
-    if (iout)
+    if (C > 1 && iout)
       for (int i = tid; i < cb * k; i += nthreads) {
         const int c = i / k, j = i - c * k;  // (positions of a batch's chunks are contiguous in the output)
         st4_out_at(iout + S + pb * k, (uint32_t)i * 4u, (uint32_t)(S + (pb + c) * L + list[c * kp + j]));

@@ -60,12 +60,15 @@ constexpr int kGroupSelMaxWaves = 8;
 //   list     receives the k kept positions, ascending; slotmap (optional) [L]: output slot
 //            of a kept token, -1 otherwise.  Visible to other wavefronts after the
 //            caller's next barrier.
+//   pos_out  (optional, global memory) [k]: receives pos0 + position of the kept tokens,
+//            ascending, stored from assembly like the kernels' other outputs
 // Order: key descending, position ascending (ties go to the lower position).
 // One barrier per digit (the digits stop as soon as the bin of the k-th key is taken
 // whole, which every wavefront sees alike) and one for the counts; every thread of the
 // workgroup must call it.
 __device__ __forceinline__ void group_topk(uint32_t key, int L, int k, uint32_t* scratch,
-                                           uint32_t* list, int32_t* slotmap, int tid, int nw) {
+                                           uint32_t* list, int32_t* slotmap, int tid, int nw,
+                                           int32_t* pos_out = nullptr, uint32_t pos0 = 0) {
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool live = tid < L;
   uint32_t* cnt = scratch + kGroupSelHist + 32;  // [kGroupSelMaxWaves][2], 16-byte aligned
@@ -157,7 +160,10 @@ __device__ __forceinline__ void group_topk(uint32_t key, int L, int k, uint32_t*
   const bool keep = gt || (eq && (eq_before + prefix_popc(me) < need));
   const uint64_t mk = __ballot(keep);
   const int slot = base + prefix_popc(mk);
-  if (keep) list[slot] = (uint32_t)tid;
+  if (keep) {
+    list[slot] = (uint32_t)tid;
+    if (pos_out) st4_out_at(pos_out, (uint32_t)slot * 4u, pos0 + (uint32_t)tid);
+  }
   if (slotmap && live) slotmap[tid] = keep ? slot : -1;
   (void)nw;
 }
@@ -181,7 +187,8 @@ template <bool PREMAX = false>
 __device__ __forceinline__ void group_score_select(float* vK, const float* vV, int L, int k,
                                                    bool do_select, float* gout, uint32_t* scratch,
                                                    uint32_t* list, int32_t* slotmap, int tid,
-                                                   int nthreads) {
+                                                   int nthreads, int32_t* pos_out = nullptr,
+                                                   uint32_t pos0 = 0) {
   const int lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
   const bool live = tid < L;
   float* red = reinterpret_cast<float*>(scratch + kGroupSelHist);  // [nw][2] maxima, then [nw][2] sums
@@ -257,7 +264,7 @@ __device__ __forceinline__ void group_score_select(float* vK, const float* vV, i
     // (a store the compiler does not know of, hence does not wait for at the barriers below)
     if (gout) st4_out_at(gout, (uint32_t)tid * 4u, __float_as_uint(s));
   }
-  if (do_select) group_topk(live ? ordered_key(s) : 0u, L, k, scratch, list, slotmap, tid, nw);
+  if (do_select) group_topk(live ? ordered_key(s) : 0u, L, k, scratch, list, slotmap, tid, nw, pos_out, pos0);
 }
 
 }  // namespace lagkv
