@@ -156,7 +156,7 @@ def kernel_name(path: int) -> str:
 
 
 def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None, cpu_streams=None,
-                   cpu_single=None, with_copy=True):
+                   cpu_single=None, with_copy=True, with_ablations=False):
     import torch
     from paper_2504_04704_amd import lagkv, synth
 
@@ -261,6 +261,22 @@ def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None
         ids = synth.stream_sample(cfg.streams, cpu_streams or args.cpu_streams)
         res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H,
                                                     cpu_single or max(1, len(ids) // 4))
+    if with_ablations and args.variant == "lag":
+        # the paper's scoring ablations (Eq. 14-15, Eq. 16) on the same resident buffers
+        abl = []
+        for vname, vid in (("local", lagkv.SCORE_LOCAL), ("l2", lagkv.SCORE_L2)):
+            def vstep():
+                lagkv.compress(K, V, cfg.S, cfg.L, cfg.r, variant=vid, out=(Ko, Vo), idx_out=idx, ws=ws, launch=launch)
+            _, vk = timed_steps(vstep, 5, 2)
+            vq = quantiles(vk)
+            valg = alg if vname == "local" else \
+                cfg.streams * (K.element_size() * cfg.D * (cfg.T + 3 * pl.T_out) + 4 * pl.T_out)
+            vp = lagkv.params_for(K, cfg.S, cfg.L, cfg.r, variant=vid, launch=launch)
+            abl.append({"variant": vname, "kernel": kernel_name(lagkv.path_for(vp, cfg.T)), "steps": 5,
+                        "ms": vq["mean"], "ms_median": vq["median"], "algorithmic_bytes": valg,
+                        "achieved_gbs": valg / (vq["mean"] * 1e-3) / 1e9,
+                        "frac": valg / (vq["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        res["config"]["scoring_ablations"] = abl
     if with_copy:
         copy = copy_rate_gbs(K, Ko)      # (overwrites the output buffers: the last thing done with them)
         roof["copy_gbs"] = copy
@@ -444,7 +460,7 @@ def summary_of(res):
 def bench_all(args):
     """The headline workload, then (unless --only-headline) configurations 2 and 3 and the decode step."""
     import torch
-    res = bench_compress(args)
+    res = bench_compress(args, with_ablations=True)
     if args.only_headline:
         return res
     torch.cuda.empty_cache()

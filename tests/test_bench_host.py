@@ -86,6 +86,12 @@ def test_default_bench_run_reports_every_workload():
     for o in others.values():
         assert 0 < o["frac"] < 1 and o["ms_p10"] <= o["ms"] <= o["ms_p90"] and o["algorithmic_bytes"] > 0
         assert o["cpu_baseline"]["kind"] == "oracle" and o["cpu_baseline"]["value"] > 0
+    for o in ("cfg2_llama8b_16k", "cfg3_llama8b_64k"):
+        assert others[o]["kernel"] == "hold_pass_kernel" and others[o]["traffic"] >= others[o]["algorithmic_bytes"]
+    abl = {a["variant"]: a for a in d["config"]["scoring_ablations"]}
+    assert set(abl) == {"local", "l2"} and all(0 < a["frac"] < 1 for a in abl.values())
+    assert abl["local"]["kernel"] == "hold_pass_kernel" and abl["local"]["algorithmic_bytes"] == 86439362560
+    assert abl["l2"]["kernel"] == "split_pass_kernel" and abl["l2"]["algorithmic_bytes"] == 60870885376
     dec = others["cfg5_decode_b32"]
     assert dec["steps"] == 64 and dec["length_after_the_first_steps"] == 8384 + 66 * 32
     assert dec["latency_ms_p50"] <= dec["latency_ms_p99"] and dec["algorithmic_bytes"] == 2684354560
