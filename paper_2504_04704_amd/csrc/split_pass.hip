@@ -300,12 +300,19 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   // Eq. 10-11 and the top-k of chunk p from the variances in vK / vV (visible to all).
   // Selection by all wavefronts needs one token per thread; otherwise one wavefront does
   // it, a different one for every chunk so that the work is spread over the SIMDs.
-  const bool group_sel = a.sel == kSelGroup && L <= nthreads;
+  // Chunks longer than 512 tokens go to all wavefronts by default (several tokens per thread):
+  // one wavefront would need the chunk's keys in LDS and a pass over them per key bit.
+  const int eg = (L + nthreads - 1) / nthreads;  // tokens per thread
+  const bool group_sel = (a.sel == kSelGroup || (a.sel == kSelAuto && L > 512)) && eg <= kGroupSelMaxKeys;
   auto select = [&](int64_t p) __attribute__((always_inline)) {
     float* g = sout ? sout + p * L : nullptr;
-    if (group_sel) group_score_select(vK, vV, L, k, gather, g, selbuf, list, nullptr, tid, nthreads);
-    else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0))
+    if (group_sel) {
+      if (eg == 1) group_score_select(vK, vV, L, k, gather, g, selbuf, list, nullptr, tid, nthreads);
+      else if (eg == 2) group_score_select_multi<2>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
+      else group_score_select_multi<4>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
+    } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
       wave_score_select_lean(vK, vV, L, k, gather, g, list, nullptr, lane);
+    }
   };
 
   if (a.variant == 2) {
@@ -338,8 +345,21 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
       __syncthreads();
       if (sout)
         for (int i = tid; i < L; i += nthreads) sout[p * L + i] = vK[i];
-      if (group_sel) group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
-      else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) wave_topk_scores(vK, L, k, list, lane);
+      if (group_sel) {
+        if (eg == 1) {
+          group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
+        } else {
+          uint32_t keys[kGroupSelMaxKeys];
+#pragma unroll
+          for (int e = 0; e < kGroupSelMaxKeys; ++e) {
+            const int t = e * nthreads + tid;
+            keys[e] = t < L ? ordered_key(vK[t]) : 0u;
+          }
+          group_topk_multi<kGroupSelMaxKeys>(keys, L, k, selbuf, list, tid, nthreads);
+        }
+      } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
+        wave_topk_scores(vK, L, k, list, lane);
+      }
       __syncthreads();
       if (gather) compact(p);
     }

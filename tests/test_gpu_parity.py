@@ -144,6 +144,27 @@ def test_selection_modes_against_oracle(select, variant, L, r, nw):
     run_and_check(K, V, 16, L, r, variant=variant, launch=hint(lagkv.PATH_FUSED, nw, 2, select=select))
 
 
+@pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
+@pytest.mark.parametrize("L,r,nw", [(1024, 0.25, 8), (640, 0.3, 8), (1500, 0.1, 8), (2048, 0.125, 8), (1024, 0.125, 4),
+                                    (600, 0.5, 2), (1024, 0.999, 8)])
+def test_long_chunks_are_selected_by_the_whole_workgroup(variant, L, r, nw):
+    """Chunks with more tokens than the workgroup has threads (the paper's L = 1024 among them):
+    several tokens per thread in the digit-histogram selection (the streaming kernel's default
+    above 512 tokens; 2, 3 or 4 tokens per thread here, 5 where a workgroup of 128 threads falls
+    back to one wavefront), with exact ties across the slabs of a thread."""
+    say("long chunks", variant, L, r, nw)
+    S = 16
+    K, V = gen(1, 2, S + 4 * L + 3, 128, torch.bfloat16, seed=L + nw)
+    # exact ties: rows duplicated across the first and the last slab of a chunk, and a run of equal rows
+    for T_ in (K, V):
+        T_[0, 0, S + L - 7] = T_[0, 0, S + 3]
+        T_[0, 0, S + L + 600 % L] = T_[0, 0, S + L + 5]
+        T_[0, 1, S + 2 * L + 100:S + 2 * L + 140] = T_[0, 1, S + 2 * L + 100]
+    for select in (lagkv.SELECT_AUTO, lagkv.SELECT_WAVE):
+        out, rep = run_and_check(K, V, S, L, r, variant=variant, launch=hint(lagkv.PATH_FUSED, nw, 2, select=select))
+        assert rep.chunks == 2 * 3
+
+
 def test_group_selection_with_many_ties():
     """Whole chunks of identical rows (every score tied) and rows duplicated in blocks: the
     histogram selection must admit ties from the lowest position up, exactly as the oracle."""
