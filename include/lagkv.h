@@ -101,8 +101,8 @@ int lagkv_keep_for_compression(int64_t T, int32_t S, int32_t L, double C, int64_
  * Device workspace, in bytes, that lagkv_compress / lagkv_append_and_compress need for
  * these parameters (p->launch included) and T rows (for append: T = cache capacity, the
  * bound that holds for any single append).  0 when the fused kernels serve the shape: rows
- * of 64, 128, 256 or 512 bytes, strides that are multiples of 16 bytes, a lag that fits
- * the LDS budget.  The three-kernel path used for every other shape stages scores and kept
+ * of 48 to 512 bytes that are a multiple of 16 bytes, strides that are multiples of 16
+ * bytes, a lag that fits the LDS budget.  The three-kernel path used for every other shape stages scores and kept
  * positions there.  The answer assumes 16-byte aligned K / V / output / cache pointers (any
  * hipMalloc'ed buffer is); a caller whose pointers are only element-aligned must ask, and
  * call, with a launch hint of LAGKV_PATH_STAGED.  Returns 0 on invalid parameters as well.
@@ -231,6 +231,7 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const v
  *             registers and reads every row once: 256-byte rows, L of 128, 256 or 512,
  *             not Eq. 16; LAGKV_ESHAPE otherwise; append calls treat it as FUSED)
  *   waves     wavefronts per workgroup of the fused kernels: 1 (append only), 2, 4 or 8
+ *             (a one-shot pass with L > 512 takes 8 only: LAGKV_ESHAPE for 2 or 4)
  *   segments  pieces each stream is cut into by the one-shot kernel, 1 .. 2^20
  * Returns -1 for a value the kernels do not support.  lagkv_workspace_bytes must be
  * asked with the same launch value as the call it sizes the workspace for.

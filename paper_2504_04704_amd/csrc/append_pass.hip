@@ -1,8 +1,9 @@
 // Decode-time LagKV kernel for gfx950: append rows to a dense cache and compress, in
 // place, every chunk of the tail that has a reference chunk.
 //
-// Row layout (shared with the one-shot kernel): a token row (D channels) is 16*LPR bytes
-// and is held by LPR consecutive lanes, 16 bytes each, so one wave64 load instruction
+// Row layout (shared with the one-shot kernel): a token row (D channels) is up to 16*LPR
+// bytes and is held by LPR consecutive lanes, 16 bytes each (lanes beyond a shorter row's
+// slices repeat its last one, see row_ops.hpp), so one wave64 load instruction
 // fetches 64/LPR whole rows and the per-token channel reductions of Eq. 10 are DPP
 // reductions over LPR lanes.  The per-channel min/max of Eq. 7-8 accumulate in
 // registers down the rows a lane visits and are folded across row groups and
@@ -28,27 +29,33 @@ struct ChanStats {
 template <int VEC>
 struct RefStats {
   TRef<VEC> K, V;
-  __device__ __forceinline__ void from(const ChanStats<VEC>& s) {
-    K.from(s.K);
-    V.from(s.V);
+  __device__ __forceinline__ void from(const ChanStats<VEC>& s, bool live) {
+    K.from(s.K, live);
+    V.from(s.V, live);
   }
 };
 
 struct Geometry {
   int lane, wave, nw;  // lane in wave, wave in workgroup, waves per workgroup
-  int rl, cl;          // row within a wave step, 16-byte column slice
+  int rl, cl;          // row within a wave step, lane within the row
+  int clc;             // 16-byte column slice of the lane (the last one again beyond the row's slices)
+  bool live;           // the lane holds channels of its own
+  int rowbytes;        // bytes of a dense row
   int rps;             // rows per workgroup step
   int row0;            // first row this lane visits
 };
 
 template <int LPR>
-__device__ __forceinline__ Geometry make_geometry() {
+__device__ __forceinline__ Geometry make_geometry(int units) {
   Geometry g;
   g.lane = threadIdx.x & 63;
   g.wave = threadIdx.x >> 6;
   g.nw = blockDim.x >> 6;
   g.rl = g.lane / LPR;
   g.cl = g.lane % LPR;
+  g.live = g.cl < units;
+  g.clc = g.live ? g.cl : units - 1;
+  g.rowbytes = units * 16;
   g.rps = g.nw * (kWave / LPR);
   g.row0 = g.wave * (kWave / LPR) + g.rl;
   return g;
@@ -65,7 +72,7 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
   constexpr int VEC = ET::VEC;
   constexpr int U = 4;
   const int n_iter = (L + g.rps - 1) / g.rps;
-  const int64_t coff = (int64_t)g.cl * 16;
+  const int64_t coff = (int64_t)g.clc * 16;
   for (int it = 0; it < n_iter; it += U) {
     uint4 kq[U], vq[U];
     int r[U];
@@ -90,8 +97,8 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
         }
       }
       if constexpr (SCORE) {
-        sgK0 = token_var<LPR, VEC>(x0, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof);
-        sgK1 = token_var<LPR, VEC>(x1, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof);
+        sgK0 = token_var<LPR, VEC>(x0, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof, g.live);
+        sgK1 = token_var<LPR, VEC>(x1, ref.K.mn, ref.K.iv, ref.K.bias, inv_D, inv_dof, g.live);
       }
       unpack<ET>(vq[u], x0);
       unpack<ET>(vq[u + 1], x1);
@@ -103,8 +110,8 @@ __device__ __forceinline__ void scan_chunk(const char* __restrict__ kp, const ch
         }
       }
       if constexpr (SCORE) {
-        sgV0 = token_var<LPR, VEC>(x0, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof);
-        sgV1 = token_var<LPR, VEC>(x1, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof);
+        sgV0 = token_var<LPR, VEC>(x0, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof, g.live);
+        sgV1 = token_var<LPR, VEC>(x1, ref.V.mn, ref.V.iv, ref.V.bias, inv_D, inv_dof, g.live);
         if (g.cl == 0) {
           if (r[u] < L) {
             sK[r[u]] = sgK0;
@@ -139,7 +146,7 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
   }
   if (g.nw > 1) {
     if (g.rl == 0) {
-      float* w = statbuf + (size_t)g.wave * 4 * D + g.cl * VEC;
+      float* w = statbuf + (size_t)g.wave * 4 * D + g.clc * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
         w[j] = acc.K.mn[j];
@@ -150,7 +157,7 @@ __device__ __forceinline__ void fold_stats(ChanStats<VEC>& acc, const Geometry& 
     }
     __syncthreads();
     for (int w = 0; w < g.nw; ++w) {
-      const float* rd = statbuf + (size_t)w * 4 * D + g.cl * VEC;
+      const float* rd = statbuf + (size_t)w * 4 * D + g.clc * VEC;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
         acc.K.mn[j] = fminf(acc.K.mn[j], rd[j]);
@@ -191,7 +198,7 @@ template <int LPR>
 __device__ __forceinline__ void move_rows_down(char* kc, char* vc, int32_t* pc, int64_t src0,
                                                int64_t dst0, int64_t nrows, const Geometry& g,
                                                int tid, int nthreads) {
-  const int64_t rowbytes = (int64_t)LPR * 16, coff = (int64_t)g.cl * 16;
+  const int64_t rowbytes = g.rowbytes, coff = (int64_t)g.clc * 16;
   constexpr int UB = 4;
   const int64_t batch = (int64_t)UB * g.rps;
   for (int64_t r0 = 0; r0 < nrows; r0 += batch) {
@@ -227,7 +234,8 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
   constexpr int VEC = ET::VEC;
   extern __shared__ float4 lds_raw[];
   char* lds = reinterpret_cast<char*>(lds_raw);
-  const Geometry g = make_geometry<LPR>();
+  const int units = (a.D * a.esize) >> 4;
+  const Geometry g = make_geometry<LPR>(units);
   const LdsLayout lay = lds_layout(a.D, a.L, a.k, g.nw);
   float* sK = reinterpret_cast<float*>(lds + lay.off_sK);
   float* sV = reinterpret_cast<float*>(lds + lay.off_sV);
@@ -237,7 +245,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int64_t stream = blockIdx.x;
   const int64_t b = stream / a.H, h = stream % a.H;
-  const int64_t rowbytes = (int64_t)LPR * 16;
+  const int64_t rowbytes = g.rowbytes;
   char* kc = a.K + stream * a.capacity * rowbytes;
   char* vc = a.V + stream * a.capacity * rowbytes;
   int32_t* pc = a.pos ? a.pos + stream * a.capacity : nullptr;
@@ -253,7 +261,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
     const char* kn = a.K_new + b * a.nsb + h * a.nsh;
     const char* vn = a.V_new + b * a.nsb + h * a.nsh;
     copy_rows_kv<LPR>(kn, vn, a.nst, kc + end0 * rowbytes, vc + end0 * rowbytes, rowbytes, a.n_new,
-                      tid, nthreads);
+                      units, tid, nthreads);
     if (pc)
       for (int64_t i = tid; i < a.n_new; i += nthreads) pc[end0 + i] = (int32_t)(a.n_seen + i);
   }
@@ -270,7 +278,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
 
   ChanStats<VEC> acc;
   RefStats<VEC> ref;
-  const int64_t coff = (int64_t)g.cl * 16;
+  const int64_t coff = (int64_t)g.clc * 16;
   for (int64_t j = 0; j < a.rounds; ++j) {
     const int64_t cur = base + j * L;      // rows of the chunk (not yet moved)
     const int64_t dst = base + j * k;      // where its kept rows go
@@ -284,6 +292,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
         float ss = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) ss = fmaf(x[i], x[i], ss);
+        if (!g.live) ss = 0.f;
         ss = group_sum<LPR>(ss);
         if (g.cl == 0 && r < L) sK[r] = -sqrtf(ss);
       }
@@ -295,7 +304,7 @@ __global__ void __launch_bounds__(512) fused_append_kernel(const AppendArgs a) {
       scan_chunk<ET, LPR, true, false>(kc + refc * rowbytes, vc + refc * rowbytes, rowbytes, L, g, acc,
                                        ref, inv_D, inv_dof, sK, sV);
       fold_stats<LPR, VEC>(acc, g, statbuf, a.D);
-      ref.from(acc);
+      ref.from(acc, g.live);
       scan_chunk<ET, LPR, false, true>(kc + cur * rowbytes, vc + cur * rowbytes, rowbytes, L, g, acc,
                                        ref, inv_D, inv_dof, sK, sV);
       __syncthreads();
@@ -368,7 +377,8 @@ __host__ __device__ inline StepLds step_lds(int D, int L, int k, int nw, int row
   return l;
 }
 
-template <typename ET, int LPR>
+// RAG: rows of fewer than LPR 16-byte slices (their size is then a run-time value).
+template <typename ET, int LPR, bool RAG>
 __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a) {
   constexpr int VEC = ET::VEC, RPW = kWave / LPR, U = 4;
   extern __shared__ float4 lds_raw[];
@@ -376,7 +386,8 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nw = nthreads >> 6, G = nw >> 1;
-  constexpr int rowbytes = LPR * 16;
+  const int units = RAG ? (a.D * a.esize) >> 4 : LPR;
+  const int rowbytes = units * 16;
   const int L = a.L, k = a.k;
   const StepLds lay = step_lds(a.D, L, k, nw, rowbytes);
   float* vK = reinterpret_cast<float*>(lds + lay.off_vK);
@@ -391,19 +402,21 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   const int tensor = wave >= G ? 1 : 0;  // 0: K rows, 1: V rows
   const int gslot = wave - tensor * G;
   const int rl = lane / LPR, cl = lane % LPR;
+  const bool live = !RAG || cl < units;
+  const int clc = live ? cl : units - 1;  // a lane beyond the row's slices repeats the last one
   const int R = G * RPW, row0 = gslot * RPW + rl;
   const int n_iter = (L + R - 1) / R;
   const int64_t stream = blockIdx.x;
   const int64_t b = stream / a.H, h = stream % a.H;
   // tail row 0 of this wavefront's tensor, at this lane's 16-byte slice
-  char* ct = (tensor ? a.V : a.K) + (stream * a.capacity + a.n_static) * rowbytes + cl * 16;
-  const char* fresh = a.n_new > 0 ? (tensor ? a.V_new : a.K_new) + b * a.nsb + h * a.nsh + cl * 16 : ct;
+  char* ct = (tensor ? a.V : a.K) + (stream * a.capacity + a.n_static) * rowbytes + clc * 16;
+  const char* fresh = a.n_new > 0 ? (tensor ? a.V_new : a.K_new) + b * a.nsb + h * a.nsh + clc * 16 : ct;
   const int n_tail = (int)a.n_tail, n_all = (int)(a.n_tail + a.n_new);
   auto src = [&](int v) -> const char* {
     return v < n_tail ? ct + (int64_t)v * rowbytes : fresh + (int64_t)(v - n_tail) * a.nst;
   };
   float* myvar = tensor ? vV : vK;
-  char* mystash = lds + lay.off_stash + (size_t)tensor * L * rowbytes + cl * 16;
+  char* mystash = lds + lay.off_stash + (size_t)tensor * L * rowbytes + clc * 16;
   int32_t* pc = a.pos ? a.pos + stream * a.capacity + a.n_static : nullptr;
   const float inv_D = 1.0f / (float)a.D;
   const float inv_dof = 1.0f / (float)(a.D - a.ddof);
@@ -460,7 +473,7 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
     }
   }
   if (rl == 0) {
-    float* w = statbuf + (size_t)wave * 2 * a.D + cl * VEC;
+    float* w = statbuf + (size_t)wave * 2 * a.D + clc * VEC;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
       w[j] = acc.mn[j];
@@ -469,7 +482,7 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
   }
   __syncthreads();
   for (int g = 0; g < G; ++g) {
-    const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
+    const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + clc * VEC;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
       acc.mn[j] = fminf(acc.mn[j], rd[j]);
@@ -477,7 +490,7 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
     }
   }
   TRef<VEC> ref;
-  ref.from(acc);
+  ref.from(acc, live);
 
   // 2. the chunk (tail rows [0,L)): channel variance of every token (Eq. 9-10), or, for
   // Eq. 16, minus the key norm (the V wavefronts then read nothing here)
@@ -489,9 +502,10 @@ __global__ void __launch_bounds__(512, 4) decode_step_kernel(const AppendArgs a)
       float ss = 0.f;
 #pragma unroll
       for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
+      if (!live) ss = 0.f;
       v = -sqrtf(group_sum<LPR>(ss));
     } else {
-      v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+      v = token_var<LPR, VEC>(x, ref.mn, ref.iv, ref.bias, inv_D, inv_dof, live);
     }
     if (cl == 0 && r < L) myvar[r] = v;
   };
@@ -618,7 +632,7 @@ constexpr size_t kStepMaxLds = 80 * 1024;
 bool decode_step_supported(const AppendArgs& a) {
   const int lpr = lanes_per_row(a.D, a.esize);
   if (lpr == 0 || a.variant == 1 || a.rounds != 1 || a.n_seen < a.S) return false;
-  return (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total <= kStepMaxLds;
+  return (size_t)step_lds(a.D, a.L, a.k, 8, row_units(a.D, a.esize) * 16).total <= kStepMaxLds;
 }
 
 template <typename KF>
@@ -636,11 +650,16 @@ static hipError_t launch_step_one(KF kernel, const AppendArgs& a, dim3 grid, dim
 template <typename ET>
 static hipError_t launch_step_t(const AppendArgs& a, int lpr, dim3 grid, dim3 block, size_t lds,
                                 hipStream_t s) {
-  switch (lpr) {
-    case 4: return launch_step_one(decode_step_kernel<ET, 4>, a, grid, block, lds, s);
-    case 8: return launch_step_one(decode_step_kernel<ET, 8>, a, grid, block, lds, s);
-    case 16: return launch_step_one(decode_step_kernel<ET, 16>, a, grid, block, lds, s);
-    case 32: return launch_step_one(decode_step_kernel<ET, 32>, a, grid, block, lds, s);
+  const bool rag = row_units(a.D, a.esize) != lpr;
+  switch (lpr * 2 + (rag ? 1 : 0)) {
+    case 8: return launch_step_one(decode_step_kernel<ET, 4, false>, a, grid, block, lds, s);
+    case 9: return launch_step_one(decode_step_kernel<ET, 4, true>, a, grid, block, lds, s);
+    case 16: return launch_step_one(decode_step_kernel<ET, 8, false>, a, grid, block, lds, s);
+    case 17: return launch_step_one(decode_step_kernel<ET, 8, true>, a, grid, block, lds, s);
+    case 32: return launch_step_one(decode_step_kernel<ET, 16, false>, a, grid, block, lds, s);
+    case 33: return launch_step_one(decode_step_kernel<ET, 16, true>, a, grid, block, lds, s);
+    case 64: return launch_step_one(decode_step_kernel<ET, 32, false>, a, grid, block, lds, s);
+    case 65: return launch_step_one(decode_step_kernel<ET, 32, true>, a, grid, block, lds, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -651,7 +670,7 @@ hipError_t launch_decode_step(const AppendArgs& a, hipStream_t s) {
   if (!decode_step_supported(a) || streams <= 0 || streams > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.n_tail + a.n_new < 2 * (int64_t)a.L || a.n_tail + a.n_new >= 3 * (int64_t)a.L)
     return hipErrorInvalidValue;
-  const size_t lds = (size_t)step_lds(a.D, a.L, a.k, 8, lpr * 16).total;
+  const size_t lds = (size_t)step_lds(a.D, a.L, a.k, 8, row_units(a.D, a.esize) * 16).total;
   const dim3 grid((unsigned)streams), block(8 * kWave);
   if (a.esize == 4) return launch_step_t<F32>(a, lpr, grid, block, lds, s);
   return a.f16 ? launch_step_t<F16>(a, lpr, grid, block, lds, s)

@@ -153,14 +153,14 @@ __global__ void __launch_bounds__(512, 2) hold_pass_kernel(const PassArgs a) {
 
   // sink rows and the sliding window (last full chunk + remainder) are plain copies
   if (gather && seg == 0 && S > 0) {
-    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, tid, nthreads);
+    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, LPR, tid, nthreads);
     if (iout)
       for (int i = tid; i < S; i += nthreads) iout[i] = i;
   }
   if (gather && seg == a.nseg - 1) {
     const int64_t w0 = S + a.n_s * L, o0 = S + a.n_s * k, nwin = a.T - w0;
     copy_rows_kv<LPR>(kin + w0 * a.st, vin + w0 * a.st, a.st, kout + o0 * rowbytes,
-                      vout + o0 * rowbytes, rowbytes, nwin, tid, nthreads);
+                      vout + o0 * rowbytes, rowbytes, nwin, LPR, tid, nthreads);
     if (iout)
       for (int64_t i = tid; i < nwin; i += nthreads) iout[o0 + i] = (int32_t)(w0 + i);
   }
@@ -535,7 +535,7 @@ static int hold_nsc(int L, int lpr) {
 
 bool hold_supported(int D, int esize, int L, int k) {
   const int lpr = lanes_per_row(D, esize);
-  if (lpr != 16) return false;
+  if (lpr != 16 || row_units(D, esize) != 16) return false;  // rows of exactly 256 bytes
   const int nsc = hold_nsc(L, lpr);
   if (!nsc) return false;
   const int R = (kHoldWaves / 2) * (kWave / lpr);

@@ -75,10 +75,13 @@ __device__ __forceinline__ float inv_range(float mn, float mx) {
 // (any error in it only enters the variance to second order, so the cheap fma form
 // seeded with bias = sum_j -(mn_j*iv_j) is used), then the centred sum of squares
 // from the exactly subtracted (x - mn).  The row is spread over LPR lanes.
+// `live`: false in a lane that holds no channels of its own (rows that do not fill LPR lanes,
+// see lanes_per_row: such a lane repeats the row's last 16 bytes and its statistics carry
+// iv = 0, so only its centred squares have to be dropped).
 template <int LPR, int VEC>
 __device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&mn)[VEC],
                                            const float (&iv)[VEC], float bias, float inv_D,
-                                           float inv_dof) {
+                                           float inv_dof, bool live = true) {
   float s = bias;
 #pragma unroll
   for (int j = 0; j < VEC; ++j) s = fmaf(x[j], iv[j], s);
@@ -90,6 +93,7 @@ __device__ __forceinline__ float token_var(const float (&x)[VEC], const float (&
     const float d = fmaf(x[j] - mn[j], iv[j], -mean);
     ss = fmaf(d, d, ss);
   }
+  if (!live) ss = 0.f;
   ss = group_sum<LPR>(ss);
   return ss * inv_dof;
 }
@@ -119,12 +123,13 @@ template <int VEC>
 struct TRef {  // reference statistics as Eq. 9 consumes them: zbar = (x - mn) * iv
   float mn[VEC], iv[VEC];
   float bias;
-  __device__ __forceinline__ void from(const TStats<VEC>& s) {
+  // live = false: a lane without channels of its own (see token_var) contributes nothing
+  __device__ __forceinline__ void from(const TStats<VEC>& s, bool live = true) {
     bias = 0.f;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
       mn[j] = s.mn[j];
-      iv[j] = inv_range(s.mn[j], s.mx[j]);
+      iv[j] = live ? inv_range(s.mn[j], s.mx[j]) : 0.f;
       bias -= mn[j] * iv[j];
     }
   }
@@ -188,13 +193,14 @@ __device__ __forceinline__ float token_var_fast(const float (&x)[VEC], const flo
   return fmaf(-s1 * inv_D, s1, s2) * inv_dof;
 }
 
-// dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane.
+// dst row r <- src row r for r < nrows, K and V together, 16 bytes per lane; rows of `units`
+// 16-byte slices (lanes beyond a row's slices repeat its last one).
 template <int LPR>
 __device__ __forceinline__ void copy_rows_kv(const char* __restrict__ ks, const char* __restrict__ vs,
                                              int64_t sst, char* __restrict__ kd,
                                              char* __restrict__ vd, int64_t dst_st, int64_t nrows,
-                                             int tid, int nthreads) {
-  const int cl = tid % LPR;
+                                             int units, int tid, int nthreads) {
+  const int cl = tid % LPR < units ? tid % LPR : units - 1;
   const int64_t ng = nthreads / LPR;
   for (int64_t r = tid / LPR; r < nrows; r += ng) {
     const uint4 a = ld16(ks + r * sst + cl * 16);
@@ -204,14 +210,17 @@ __device__ __forceinline__ void copy_rows_kv(const char* __restrict__ ks, const 
   }
 }
 
+// Rows the fused kernels take: whole 16-byte slices, 48 to 512 bytes.  A row is held by
+// LPR = 4, 8, 16 or 32 consecutive lanes, 16 bytes each; when its `units` slices do not fill
+// them, the lanes left over repeat the last slice (loads and stores of the same bytes twice are
+// harmless, min/max do not change) and are left out of the sums over the channels.
+inline int row_units(int D, int esize) {
+  const int64_t bytes = (int64_t)D * esize;
+  return (bytes % 16 == 0 && bytes >= 48 && bytes <= 512) ? (int)(bytes / 16) : 0;
+}
 inline int lanes_per_row(int D, int esize) {
-  switch ((int64_t)D * esize) {
-    case 64: return 4;
-    case 128: return 8;
-    case 256: return 16;
-    case 512: return 32;
-    default: return 0;
-  }
+  const int u = row_units(D, esize);
+  return u == 0 ? 0 : u <= 4 ? 4 : u <= 8 ? 8 : u <= 16 ? 16 : 32;
 }
 
 }  // namespace lagkv

@@ -73,12 +73,16 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   const int tensor = wave >= G ? 1 : 0;  // 0: this wavefront handles K rows, 1: V rows
   const int gslot = wave - tensor * G;
   const int rl = lane / LPR, cl = lane % LPR;
+  // rows of `units` 16-byte slices: a lane beyond them repeats the last slice (row_ops.hpp)
+  const int units = (a.D * a.esize) >> 4;
+  const bool live = cl < units;
+  const int clc = live ? cl : units - 1;
   const int R = G * RPW;                  // rows of one tensor covered per step
   const int row0 = gslot * RPW + rl;
   const int L = a.L, k = a.k, S = a.S;
   const int n_iter = (L + R - 1) / R;
-  const int64_t rowbytes = (int64_t)LPR * 16;
-  const int64_t coff = (int64_t)cl * 16;
+  const int64_t rowbytes = (int64_t)units * 16;
+  const int64_t coff = (int64_t)clc * 16;
 
   const int64_t stream = stream_of(blockIdx.x / a.nseg, (int64_t)a.B * a.H, a.order);
   const int seg = blockIdx.x % a.nseg;
@@ -101,14 +105,14 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
 
   // sink rows and the sliding window (last full chunk + remainder) are plain copies
   if (gather && seg == 0 && S > 0) {
-    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, tid, nthreads);
+    copy_rows_kv<LPR>(kin, vin, a.st, kout, vout, rowbytes, S, units, tid, nthreads);
     if (iout)
       for (int i = tid; i < S; i += nthreads) iout[i] = i;
   }
   if (gather && seg == a.nseg - 1) {
     const int64_t w0 = S + a.n_s * L, o0 = S + a.n_s * k, nwin = a.T - w0;
     copy_rows_kv<LPR>(kin + w0 * a.st, vin + w0 * a.st, a.st, kout + o0 * rowbytes,
-                      vout + o0 * rowbytes, rowbytes, nwin, tid, nthreads);
+                      vout + o0 * rowbytes, rowbytes, nwin, units, tid, nthreads);
     if (iout)
       for (int64_t i = tid; i < nwin; i += nthreads) iout[o0 + i] = (int32_t)(w0 + i);
   }
@@ -124,7 +128,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   // 32-bit lane offset, so no per-lane address arithmetic is needed; steps past the end
   // repeat the last step.  Otherwise rows past L repeat the last row, lane by lane.
   constexpr bool exact = EXACT;
-  const uint32_t lane_off = (uint32_t)(row0 * a.st) + (uint32_t)cl * 16u;
+  const uint32_t lane_off = (uint32_t)(row0 * a.st) + (uint32_t)clc * 16u;
   // consume U loaded rows whose first step is `it` (rows of steps past the end are skipped)
   auto consume = [&](const uint4 (&q)[U], const int (&r)[U], auto stats_tag, auto score_tag)
                      __attribute__((always_inline)) {
@@ -142,8 +146,8 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         }
       }
       if constexpr (SCORE) {
-        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof, live);
+        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof, live);
         if (cl == 0) {
           if (r[u] < L) myvar[r[u]] = v0;
           if (r[u + 1] < L) myvar[r[u + 1]] = v1;
@@ -204,8 +208,8 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         }
       }
       if constexpr (SCORE) {
-        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
-        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof);
+        const float v0 = token_var<LPR, VEC>(x0, ref.mn, ref.iv, ref.bias, inv_D, inv_dof, live);
+        const float v1 = token_var<LPR, VEC>(x1, ref.mn, ref.iv, ref.bias, inv_D, inv_dof, live);
         if (cl == 0) {
           lds_store_f32(var_lds + (uint32_t)(phys(s) * R) * 4u, v0);
           if (s + 1 < n_iter) lds_store_f32(var_lds + (uint32_t)(phys(s + 1) * R) * 4u, v1);
@@ -252,7 +256,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
     }
     if (G > 1) {
       if (rl == 0) {
-        float* w = statbuf + (size_t)wave * 2 * a.D + cl * VEC;
+        float* w = statbuf + (size_t)wave * 2 * a.D + clc * VEC;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
           w[j] = acc.mn[j];
@@ -261,7 +265,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
       }
       __syncthreads();
       for (int g = 0; g < G; ++g) {
-        const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + cl * VEC;
+        const float* rd = statbuf + (size_t)(tensor * G + g) * 2 * a.D + clc * VEC;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
           acc.mn[j] = fminf(acc.mn[j], rd[j]);
@@ -302,14 +306,17 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   // it, a different one for every chunk so that the work is spread over the SIMDs.
   // Chunks longer than 512 tokens go to all wavefronts by default (several tokens per thread):
   // one wavefront would need the chunk's keys in LDS and a pass over them per key bit.
+  // (The variant with asynchronous loads stops at two tokens per thread; it never needs more with
+  // the launch shapes the library chooses, and is not instantiated with more.)
   const int eg = (L + nthreads - 1) / nthreads;  // tokens per thread
-  const bool group_sel = (a.sel == kSelGroup || (a.sel == kSelAuto && L > 512)) && eg <= kGroupSelMaxKeys;
+  constexpr int max_eg = use_dma ? 2 : kGroupSelMaxKeys;
+  const bool group_sel = (a.sel == kSelGroup || (a.sel == kSelAuto && L > 512)) && eg <= max_eg;
   auto select = [&](int64_t p) __attribute__((always_inline)) {
     float* g = sout ? sout + p * L : nullptr;
     if (group_sel) {
       if (eg == 1) group_score_select(vK, vV, L, k, gather, g, selbuf, list, nullptr, tid, nthreads);
       else if (eg == 2) group_score_select_multi<2>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
-      else group_score_select_multi<4>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
+      else if constexpr (max_eg > 2) group_score_select_multi<4>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
     } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
       wave_score_select_lean(vK, vV, L, k, gather, g, list, nullptr, lane);
     }
@@ -337,6 +344,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
           float ss = 0.f;
 #pragma unroll
           for (int j = 0; j < VEC; ++j) ss = fmaf(x[j], x[j], ss);
+          if (!live) ss = 0.f;
           ss = group_sum<LPR>(ss);
           if (cl == 0 && r[u] < L) vK[r[u]] = -sqrtf(ss);
         }
@@ -349,13 +357,13 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         if (eg == 1) {
           group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
         } else {
-          uint32_t keys[kGroupSelMaxKeys];
+          uint32_t keys[max_eg];
 #pragma unroll
-          for (int e = 0; e < kGroupSelMaxKeys; ++e) {
+          for (int e = 0; e < max_eg; ++e) {
             const int t = e * nthreads + tid;
             keys[e] = t < L ? ordered_key(vK[t]) : 0u;
           }
-          group_topk_multi<kGroupSelMaxKeys>(keys, L, k, selbuf, list, tid, nthreads);
+          group_topk_multi<max_eg>(keys, L, k, selbuf, list, tid, nthreads);
         }
       } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
         wave_topk_scores(vK, L, k, list, lane);
@@ -372,7 +380,7 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
       acc.reset();
       scan(crow, false, T_{}, F_{});
       fold();
-      ref.from(acc);
+      ref.from(acc, live);
       scan(crow, LAGKV_LOCAL_REV != 0, F_{}, T_{});
       __syncthreads();
       select(p);
@@ -386,13 +394,13 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   acc.reset();
   scan(S + p1 * L, false, T_{}, F_{});
   fold();
-  ref.from(acc);
+  ref.from(acc, live);
   __syncthreads();  // statbuf is rewritten by the next fold
   for (int64_t p = p1 - 1; p >= p0; --p) {
     acc.reset();
     scan(S + p * L, false, T_{}, T_{});
     fold();  // barrier inside: the variances are visible
-    ref.from(acc);  // chunk p is the reference of chunk p-1 (done before the selection so
+    ref.from(acc, live);  // chunk p is the reference of chunk p-1 (done before the selection so
                     // that the running statistics are dead across it: fewer live registers)
     select(p);
     __syncthreads();

@@ -156,7 +156,7 @@ def test_calls_reject_bad_arguments_before_touching_the_device(lib):
     assert lib.lagkv_compress(C.byref(bad_stride), fake, fake, 1024, fake, fake, None, None, None, 0,
                               None) == lagkv.ESHAPE
     # a shape only the three-kernel path serves needs a workspace
-    odd = lagkv.make_params(1, 2, 40, 16, 128, 0.5, lagkv.F32)
+    odd = lagkv.make_params(1, 2, 42, 16, 128, 0.5, lagkv.F32)
     need = lagkv.workspace_bytes(odd, 1024)
     assert need > 0 and lagkv.workspace_bytes(p, 1024) == 0
     assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, None, 0,
@@ -164,7 +164,7 @@ def test_calls_reject_bad_arguments_before_touching_the_device(lib):
     assert lib.lagkv_compress(C.byref(odd), fake, fake, 1024, fake, fake, None, None, fake, 64,
                               None) == lagkv.EWORKSPACE
     # forcing the fused kernels on a shape they do not cover is an error, not a fallback
-    forced = lagkv.make_params(1, 2, 40, 16, 128, 0.5, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))
+    forced = lagkv.make_params(1, 2, 42, 16, 128, 0.5, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))
     assert lib.lagkv_compress(C.byref(forced), fake, fake, 1024, fake, fake, None, None, fake, need,
                               None) == lagkv.ESHAPE
     # the staged path asked for by hint needs its workspace even on a fused shape, and says so
@@ -235,10 +235,20 @@ def test_path_for_names_the_kernels_of_a_call(lib):
             == lagkv.PATH_STAGED
     assert lagkv.path_for(mk(2, 8, 128, 16, 100, 0.25, lagkv.BF16), T) == lagkv.PATH_FUSED
     assert lagkv.path_for(mk(2, 8, 128, 16, 512, 0.25, lagkv.F32), T) == lagkv.PATH_FUSED      # rows of 512 bytes
-    assert lagkv.path_for(mk(2, 8, 40, 16, 128, 0.25, lagkv.F32), T) == lagkv.PATH_STAGED      # rows of 160 bytes
+    assert lagkv.path_for(mk(2, 8, 40, 16, 128, 0.25, lagkv.F32), T) == lagkv.PATH_FUSED       # rows of 160 bytes
+    assert lagkv.path_for(mk(2, 8, 96, 16, 128, 0.25, lagkv.BF16), T) == lagkv.PATH_FUSED      # rows of 192 bytes
+    assert lagkv.path_for(mk(2, 8, 24, 16, 128, 0.25, lagkv.BF16), T) == lagkv.PATH_FUSED      # rows of 48 bytes
+    assert lagkv.path_for(mk(2, 8, 16, 16, 128, 0.25, lagkv.BF16), T) == lagkv.PATH_STAGED     # rows of 32 bytes
+    assert lagkv.path_for(mk(2, 8, 42, 16, 128, 0.25, lagkv.F32), T) == lagkv.PATH_STAGED      # rows of 168 bytes
+    assert lagkv.path_for(mk(2, 8, 264, 16, 128, 0.25, lagkv.BF16), T) == lagkv.PATH_STAGED    # rows of 528 bytes
     for bad in (mk(2, 8, 128, 16, 100, 0.25, lagkv.BF16, launch=lagkv.launch_hint(lagkv.PATH_RESIDENT)),
-                mk(2, 8, 40, 16, 128, 0.25, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))):
+                mk(2, 8, 42, 16, 128, 0.25, lagkv.F32, launch=lagkv.launch_hint(lagkv.PATH_FUSED))):
         assert lib.lagkv_path_for(C.byref(bad), T) == -lagkv.ESHAPE
+    # lags above 512 tokens run with eight wavefronts only
+    for L, nw, want in ((1024, 4, -lagkv.ESHAPE), (600, 2, -lagkv.ESHAPE), (1024, 8, lagkv.PATH_FUSED),
+                        (1024, 0, lagkv.PATH_FUSED), (512, 4, lagkv.PATH_FUSED)):
+        hinted = mk(2, 8, 128, 16, L, 0.25, lagkv.BF16, launch=lagkv.launch_hint(lagkv.PATH_FUSED, nw))
+        assert lib.lagkv_path_for(C.byref(hinted), 16 + 8 * 1024) == want
     assert lib.lagkv_path_for(C.byref(mk(2, 8, 128, 16, 128, 0.001, lagkv.BF16)), T) == -lagkv.EINVAL
     assert lib.lagkv_path_for(C.byref(mk(2, 8, 128, 16, 128, 0.25, lagkv.BF16)), 0) == -lagkv.ESHAPE
 

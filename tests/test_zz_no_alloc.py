@@ -46,12 +46,12 @@ def _both(K, V, S, L, r, variant, launch=0):
 @pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
 def test_static_scratch_two_calls_in_a_row_second_one_smaller(variant):
     lagkv.load()
-    # 192-byte rows (D = 96 bf16): only the three-kernel path serves them, so the scratch is used
-    K, V = _gen(3, 4, 16 + 9 * 64 + 21, 96, torch.bfloat16, seed=7)
+    # 200-byte rows (D = 100 bf16): only the three-kernel path serves them, so the scratch is used
+    K, V = _gen(3, 4, 16 + 9 * 64 + 21, 100, torch.bfloat16, seed=7)
     assert lagkv.workspace_bytes(lagkv.params_for(K, 16, 64, 0.25), K.shape[2]) > 0
     _both(K, V, 16, 64, 0.25, variant)
     # second call: fewer streams, shorter, another lag; the array still holds the first call's data
-    K2, V2 = _gen(1, 2, 8 + 4 * 50 + 3, 96, torch.bfloat16, seed=8)
+    K2, V2 = _gen(1, 2, 8 + 4 * 50 + 3, 100, torch.bfloat16, seed=8)
     _both(K2, V2, 8, 50, 0.3, variant)
     # and a larger one again
     _both(K, V, 16, 64, 0.25, variant)
@@ -70,7 +70,7 @@ def test_static_scratch_staged_by_hint_and_fused_shapes():
 def test_static_scratch_rejects_sizes_beyond_its_limit():
     lib = lagkv.load()
     # 64 streams x 4 chunks x (L + k) x 4 B would fit; this one needs about 40 MiB
-    p = lagkv.make_params(64, 8, 96, 16, 128, 0.25, lagkv.BF16)
+    p = lagkv.make_params(64, 8, 100, 16, 128, 0.25, lagkv.BF16)
     T = 16 + 128 * 160
     assert lagkv.workspace_bytes(p, T) > lagkv.STATIC_SCRATCH_BYTES
     fake = 0x1000                                               # never dereferenced: the size check comes first
