@@ -167,9 +167,16 @@ def test_selection_modes_against_oracle(select, variant, L, r, nw):
     run_and_check(K, V, 16, L, r, variant=variant, launch=hint(lagkv.PATH_FUSED, nw, 2, select=select))
 
 
+# (1024, 0.125, 4): L = 1024 forced to 4 wavefronts once ended in a GPU memory fault whose cause was not found; the
+# library now refuses that launch shape, and the case stays here, skipped, so that it is not forgotten
+_FAULTED = pytest.mark.skip(reason="launch shape switched off after a memory fault of unknown cause; the library "
+                                   "refuses it (test_long_chunks_take_eight_wavefronts_only)")
+
+
 @pytest.mark.parametrize("variant", [lagkv.SCORE_LAG, lagkv.SCORE_LOCAL, lagkv.SCORE_L2])
 @pytest.mark.parametrize("L,r,nw", [(1024, 0.25, 8), (640, 0.3, 8), (1500, 0.1, 8), (2048, 0.125, 8), (1024, 0.125, 0),
-                                    (600, 0.5, 8), (1024, 0.999, 8)])
+                                    (600, 0.5, 8), (1024, 0.999, 8),
+                                    pytest.param(1024, 0.125, 4, marks=_FAULTED)])
 def test_long_chunks_are_selected_by_the_whole_workgroup(variant, L, r, nw):
     """Chunks with more tokens than the workgroup has threads (the paper's L = 1024 among them):
     several tokens per thread in the digit-histogram selection (the streaming kernel's default
