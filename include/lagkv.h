@@ -231,7 +231,6 @@ int lagkv_append_and_compress(const lagkv_params* p, lagkv_cache* cache, const v
  *             registers and reads every row once: 256-byte rows, L of 128, 256 or 512,
  *             not Eq. 16; LAGKV_ESHAPE otherwise; append calls treat it as FUSED)
  *   waves     wavefronts per workgroup of the fused kernels: 1 (append only), 2, 4 or 8
- *             (a one-shot pass with L > 512 takes 8 only: LAGKV_ESHAPE for 2 or 4)
  *   segments  pieces each stream is cut into by the one-shot kernel, 1 .. 2^20
  * Returns -1 for a value the kernels do not support.  lagkv_workspace_bytes must be
  * asked with the same launch value as the call it sizes the workspace for.

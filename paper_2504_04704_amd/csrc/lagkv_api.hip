@@ -128,13 +128,6 @@ bool staged_fits(const Norm& n) {
 // (fold, selection by one wavefront, barriers) weighs more, and smaller workgroups - more of
 // them per CU, each with its own selection - overlap it better (measured: L=128 0.59 ms with 2
 // against 0.80 ms with 8 wavefronts on 256 streams of 16K rows).
-// Chunks of more than 512 tokens run with eight wavefronts only: a hint that asks for smaller
-// workgroups there is refused (the launch shapes it would select - the asynchronous-load
-// variant with three or four tokens per thread in the selection - are switched off).
-bool split_waves_hint_ok(const Norm& n) {
-  return n.L <= 512 || (n.hint.waves != 2 && n.hint.waves != 4);
-}
-
 int split_nw(const Norm& n) {
   int nw = n.L >= 512 ? 8 : n.L >= 256 ? 4 : 2;
   const int t = n.hint.waves;
@@ -195,7 +188,6 @@ int launch_fused_any(PassArgs& a, const Norm& n, hipStream_t s) {
     return launch_hold_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
   }
   if (n.hint.path == LAGKV_PATH_RESIDENT) return LAGKV_ESHAPE;
-  if (!split_waves_hint_ok(n)) return LAGKV_ESHAPE;
   a.nwaves = split_nw(n);
   a.nseg = pick_segments_split(n, a.n_s, a.nwaves);
   return launch_split_pass(a, s) == hipSuccess ? LAGKV_OK : LAGKV_EHIP;
@@ -620,8 +612,7 @@ int lagkv_path_for(const lagkv_params* p, int64_t T) {
   if ((force == LAGKV_PATH_FUSED || force == LAGKV_PATH_RESIDENT) && !fused_ok) return -LAGKV_ESHAPE;
   if (fused_ok && force != LAGKV_PATH_STAGED) {
     if (use_resident(n)) return LAGKV_PATH_RESIDENT;
-    if (force == LAGKV_PATH_RESIDENT || !split_waves_hint_ok(n)) return -LAGKV_ESHAPE;
-    return LAGKV_PATH_FUSED;
+    return force == LAGKV_PATH_RESIDENT ? -LAGKV_ESHAPE : LAGKV_PATH_FUSED;
   }
   return staged_fits(n) ? LAGKV_PATH_STAGED : -LAGKV_ESHAPE;
 }

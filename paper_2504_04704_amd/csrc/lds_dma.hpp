@@ -104,11 +104,12 @@ __device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)
 #define LAGKV_DMA16_FLAGS "nt"
 #endif
 __device__ __forceinline__ void dma_rows16(uint32_t lane_off, const char* sbase, uint32_t lds_addr) {
+  uint64_t base;  // (see sgpr_base_note below; the copy is also the wait state after the write of M0)
   asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1 " LAGKV_DMA16_FLAGS
-      :
+      "s_mov_b32 m0, %3\n\t"
+      "s_mov_b64 %0, %2\n\t"
+      "global_load_lds_dwordx4 %1, %0 " LAGKV_DMA16_FLAGS
+      : "=&s"(base)
       : "v"(lane_off), "s"(sbase), "s"(lds_addr)
       : "memory");
 }
@@ -119,16 +120,29 @@ __device__ __forceinline__ void st4_out(void* p, uint32_t v) {
 }
 // The same stores with a wave-uniform base and a 32-bit lane offset (one address register
 // instead of two).
+// sgpr_base_note: a vector-memory instruction must not read a scalar register within five wait
+// states of a VECTOR instruction that wrote it (v_readlane / v_readfirstlane - which is how the
+// compiler brings back a base address it had to park in a vector register).  The compiler
+// inserts those wait states for its own instructions but cannot see into an asm block, so a
+// base handed to these blocks is first copied by a SCALAR move (interlocked in hardware on its
+// read side, and a scalar write needs no wait before a vector-memory read): without the copy
+// the store could go out with a stale half of its address.
 __device__ __forceinline__ void st16_out_at(char* sbase, uint32_t voff, const uint4& v) {
   typedef uint32_t vec4_t __attribute__((ext_vector_type(4)));
   const vec4_t q = {v.x, v.y, v.z, v.w};
 #ifndef LAGKV_STORE_AT_FLAGS
 #define LAGKV_STORE_AT_FLAGS "sc0 nt"
 #endif
-  asm volatile("global_store_dwordx4 %0, %1, %2 " LAGKV_STORE_AT_FLAGS ::"v"(voff), "v"(q), "s"(sbase) : "memory");
+  uint64_t base;
+  asm volatile("s_mov_b64 %0, %3\n\tglobal_store_dwordx4 %1, %2, %0 " LAGKV_STORE_AT_FLAGS
+               : "=&s"(base)
+               : "v"(voff), "v"(q), "s"(sbase)
+               : "memory");
 }
+// (Scores and positions: once per token, not per row slice - here the five wait states are
+// simply spent, which holds whatever wrote the registers before.)
 __device__ __forceinline__ void st4_out_at(void* sbase, uint32_t voff, uint32_t v) {
-  asm volatile("global_store_dword %0, %1, %2" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
+  asm volatile("s_nop 4\n\tglobal_store_dword %0, %1, %2" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
 }
 
 

@@ -306,17 +306,14 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
   // it, a different one for every chunk so that the work is spread over the SIMDs.
   // Chunks longer than 512 tokens go to all wavefronts by default (several tokens per thread):
   // one wavefront would need the chunk's keys in LDS and a pass over them per key bit.
-  // (The variant with asynchronous loads stops at two tokens per thread; it never needs more with
-  // the launch shapes the library chooses, and is not instantiated with more.)
   const int eg = (L + nthreads - 1) / nthreads;  // tokens per thread
-  constexpr int max_eg = use_dma ? 2 : kGroupSelMaxKeys;
-  const bool group_sel = (a.sel == kSelGroup || (a.sel == kSelAuto && L > 512)) && eg <= max_eg;
+  const bool group_sel = (a.sel == kSelGroup || (a.sel == kSelAuto && L > 512)) && eg <= kGroupSelMaxKeys;
   auto select = [&](int64_t p) __attribute__((always_inline)) {
     float* g = sout ? sout + p * L : nullptr;
     if (group_sel) {
       if (eg == 1) group_score_select(vK, vV, L, k, gather, g, selbuf, list, nullptr, tid, nthreads);
       else if (eg == 2) group_score_select_multi<2>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
-      else if constexpr (max_eg > 2) group_score_select_multi<4>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
+      else group_score_select_multi<4>(vK, vV, L, k, gather, g, selbuf, list, tid, nthreads);
     } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
       wave_score_select_lean(vK, vV, L, k, gather, g, list, nullptr, lane);
     }
@@ -357,13 +354,13 @@ __global__ void __launch_bounds__(512, LAGKV_SPLIT_WPE) split_pass_kernel(const 
         if (eg == 1) {
           group_topk(tid < L ? ordered_key(vK[tid]) : 0u, L, k, selbuf, list, nullptr, tid, nw);
         } else {
-          uint32_t keys[max_eg];
+          uint32_t keys[kGroupSelMaxKeys];
 #pragma unroll
-          for (int e = 0; e < max_eg; ++e) {
+          for (int e = 0; e < kGroupSelMaxKeys; ++e) {
             const int t = e * nthreads + tid;
             keys[e] = t < L ? ordered_key(vK[t]) : 0u;
           }
-          group_topk_multi<max_eg>(keys, L, k, selbuf, list, tid, nthreads);
+          group_topk_multi<kGroupSelMaxKeys>(keys, L, k, selbuf, list, tid, nthreads);
         }
       } else if (wave == (a.sel == kSelWave ? (int)(p % nw) : 0)) {
         wave_topk_scores(vK, L, k, list, lane);
