@@ -9,6 +9,10 @@ written by a vector instruction fewer than five wait states earlier (counted con
 move that rewrites the register in between does not end the search, exactly as the compiler's own
 hazard recogniser counts).
 
+A second rule of the same kind: a store of more than 64 bits reads its data registers over two more
+cycles, so a vector-ALU instruction must not overwrite them within two wait states of the store;
+`scan_store_data` finds asm-block stores that a vector-ALU write of their data follows too closely.
+
     python -m paper_2504_04704_amd.isa_check            # compiles the kernel sources and scans them
 """
 from __future__ import annotations
@@ -97,6 +101,56 @@ def scan(asm: str) -> List[Site]:
     return sites
 
 
+STORE_DATA_WAIT_STATES = 2
+_WIDE_STORE = re.compile(r"^(global|flat|scratch)_store_dwordx[34]\b")
+
+
+def _vector_regs(text: str) -> set:
+    regs = set()
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]", text):
+        regs.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r"\bv(\d+)\b", text):
+        regs.add(int(m.group(1)))
+    return regs
+
+
+def scan_store_data(asm: str) -> List[Site]:
+    sites = []
+    function, in_asm = "?", False
+    pending = []  # (data registers, wait states since the store, text)
+    for no, raw in enumerate(asm.split("\n"), 1):
+        s = raw.strip()
+        m = _LABEL.match(s)
+        if m:
+            function, pending = m.group(1), []
+            continue
+        if "#ASMSTART" in s:
+            in_asm = True
+            continue
+        if "#ASMEND" in s:
+            in_asm = False
+            continue
+        if not s or s[0] in ";." or s.endswith(":"):
+            continue
+        nop = re.match(r"s_nop\s+(\d+)", s)
+        states = int(nop.group(1)) + 1 if nop else 1
+        written = set()
+        if s.startswith("v_"):
+            parts = s.split(None, 1)
+            written = _vector_regs(parts[1].split(",")[0]) if len(parts) > 1 else set()
+        still = []
+        for data, waited, text in pending:
+            if written & data:
+                sites.append(Site(no, function, text, waited, s))
+            elif waited + states < STORE_DATA_WAIT_STATES:
+                still.append((data, waited + states, text))
+        pending = still
+        if in_asm and _WIDE_STORE.match(s):
+            operands = s.split(None, 1)[1].split(",")
+            pending.append((_vector_regs(operands[1]), 0, s))
+    return sites
+
+
 def assembly_of(source: str) -> str:
     """gfx950 assembly of one file of csrc/, with the library's own compile flags."""
     with tempfile.TemporaryDirectory(prefix="lagkv_isa_") as tmp:
@@ -112,7 +166,10 @@ def assembly_of(source: str) -> str:
 
 def check_sources(sources=KERNEL_SOURCES) -> dict:
     with ThreadPoolExecutor(min(len(sources), os.cpu_count() or 1)) as ex:
-        return dict(zip(sources, ex.map(lambda s: scan(assembly_of(s)), sources)))
+        def both(src):
+            asm = assembly_of(src)
+            return scan(asm) + scan_store_data(asm)
+        return dict(zip(sources, ex.map(both, sources)))
 
 
 if __name__ == "__main__":

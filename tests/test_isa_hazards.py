@@ -47,6 +47,18 @@ def test_checker_accepts_padded_and_scalar_written_bases():
     assert len(s) == 1 and s[0].wait_states == 1
 
 
+def test_checker_finds_a_vector_write_of_the_data_of_a_wide_store():
+    store = "\t;;#ASMSTART\n\tglobal_store_dwordx4 v130, v[30:33], s[10:11] sc0 nt\n\t;;#ASMEND\n"
+    find = lambda body: isa_check.scan_store_data(HEAD + body)
+    assert len(find(store + "\tv_mov_b32_e32 v31, v2\n")) == 1
+    assert len(find(store + "\ts_or_b64 exec, exec, s[8:9]\n\tv_lshlrev_b32_e32 v33, 2, v1\n")) == 1
+    assert find(store + "\ts_or_b64 exec, exec, s[8:9]\n\tv_cmp_lt_i32_e32 vcc, -1, v131\n\tv_mov_b32_e32 v31, v2\n") == []
+    assert find(store + "\ts_nop 1\n\tv_mov_b32_e32 v31, v2\n") == []
+    assert find(store + "\tv_mov_b32_e32 v34, v2\n\tv_mov_b32_e32 v29, v2\n") == []          # other registers
+    assert find(store + "\tds_read_b128 v[30:33], v5\n") == []                                   # not a vector-ALU write
+    assert find("\t;;#ASMSTART\n\tglobal_store_dword v95, v0, s[8:9]\n\t;;#ASMEND\n\tv_mov_b32_e32 v0, v2\n") == []   # 32 bits
+
+
 def test_kernel_sources_have_no_such_place():
     found = isa_check.check_sources()
     assert set(found) == set(isa_check.KERNEL_SOURCES)
