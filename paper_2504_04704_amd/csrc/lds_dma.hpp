@@ -95,8 +95,10 @@ __device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)
 // barriers: the compiler does not know of it and so never waits for it on its own (a load it
 // knows of is drained at the next fence).  Lane l's 16 bytes at sbase + lane_off are written
 // to LDS at lds_addr + 16*l; sbase and lds_addr are wave-uniform.  M0 carries the LDS address
-// (the compiler reserves M0 and re-loads it before each of its own uses; the s_nop covers the
-// wait state between the write of M0 and the load that reads it).
+// (M0 is a reserved register to the compiler: it holds nothing there across a statement and
+// loads it again before each of its own uses, so the block need not - and cannot - name it as
+// clobbered; the scalar copy of the base stands between the write of M0 and the load that
+// reads it, which needs one wait state).
 // The rows it loads are read exactly once by the kernel that uses it (the register-resident
 // one), hence non-temporal: measured 14.39 against 14.64 ms on the 128K workload ("sc0 nt"
 // the same, "sc1" no gain).
