@@ -468,7 +468,7 @@ def bench_all(args):
     t0 = time.perf_counter()
     # the 16K cache in full and a quarter of the 64K one on the host: a few seconds of oracle each
     for name, cpu_n in (("cfg2_llama8b_16k", 256), ("cfg3_llama8b_64k", 64)):
-        r = bench_compress(args, cfg_name=name, steps=max(args.steps, 20), warmup=3, placements=2,
+        r = bench_compress(args, cfg_name=name, steps=max(args.steps, 20), warmup=3, placements=min(args.placements, 6),
                            cpu_streams=cpu_n, cpu_single=8)
         others.append(summary_of(r))
         torch.cuda.empty_cache()
