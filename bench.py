@@ -158,7 +158,7 @@ def kernel_name(path: int) -> str:
 def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None, cpu_streams=None,
                    cpu_single=None, with_copy=True, with_ablations=False):
     import torch
-    from paper_2504_04704_amd import lagkv, synth
+    from paper_2504_04704_amd import lagkv, placement, synth
 
     cfg = synth.CONFIGS[cfg_name or args.config]
     steps = steps or args.steps
@@ -194,24 +194,15 @@ def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None
     # distinct speeds from one allocation of the working set to the next, the first allocation
     # on a freshly started GPU always being the slowest.  A server allocates its cache once and
     # keeps it, so it can afford to look for a good placement at start-up; the bench does the
-    # same: it builds the working set `--placements` times, times three launches on each, and
-    # keeps the fastest set (the others are released).  Every trial is reported in
+    # same (placement.pick): it builds the working set `--placements` times, times three launches on each,
+    # and keeps the fastest set (the others are released).  Every trial is reported in
     # config.placement_trials_ms, and roofline carries the first-allocation and the
     # median-of-trials fractions beside the kept one; the K timed steps all run on the kept buffers.
-    trials = []
-    best = None
     t0 = time.perf_counter()
-    for _ in range(1 if args.no_page_warmup else max(1, placements)):
-        cand = build_working_set()
-        ms = quick_ms(cand)
-        trials.append(round(ms, 4))
-        if best is None or ms < best[0]:
-            best = (ms, cand)
-        del cand
-        torch.cuda.empty_cache()
-    K, V, Ko, Vo, idx, p, pl = best[1]
-    del best
-    torch.cuda.empty_cache()
+    (K, V, Ko, Vo, idx, p, pl), trials = placement.pick(build_working_set, quick_ms,
+                                                         1 if args.no_page_warmup else placements,
+                                                         torch.cuda.empty_cache)
+    trials = [round(ms, 4) for ms in trials]
     print(f"[bench] {cfg.name}: {2 * K.numel() * K.element_size() / 2**30:.1f} GiB of KV, placement trials "
           f"{trials} ms in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
 

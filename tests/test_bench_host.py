@@ -95,3 +95,24 @@ def test_default_bench_run_reports_every_workload():
     dec = others["cfg5_decode_b32"]
     assert dec["steps"] == 64 and dec["length_after_the_first_steps"] == 8384 + 66 * 32
     assert dec["latency_ms_p50"] <= dec["latency_ms_p99"] and dec["algorithmic_bytes"] == 2684354560
+
+
+def test_placement_pick_keeps_the_fastest_set_and_reports_every_trial():
+    from paper_2504_04704_amd import placement
+    speeds = iter([16.4, 14.1, 14.8, 16.3])
+    built, released = [], []
+
+    def build():
+        built.append(object())
+        return built[-1]
+
+    times = {}
+
+    def time_ms(ws):
+        times[id(ws)] = next(speeds)
+        return times[id(ws)]
+
+    kept, trials = placement.pick(build, time_ms, trials=4, release=lambda: released.append(1))
+    assert trials == [16.4, 14.1, 14.8, 16.3] and kept is built[1] and len(built) == 4 and len(released) == 5
+    kept, trials = placement.pick(lambda: "only", lambda ws: 3.0, trials=0)       # at least one allocation
+    assert kept == "only" and trials == [3.0]
