@@ -116,12 +116,8 @@ __device__ __forceinline__ void dma_rows16(uint32_t lane_off, const char* sbase,
       : "memory");
 }
 
-// 4-byte store of an output position, issued like st16_out (not known to the compiler).
-__device__ __forceinline__ void st4_out(void* p, uint32_t v) {
-  asm volatile("global_store_dword %0, %1, off" ::"v"(p), "v"(v) : "memory");
-}
-// The same stores with a wave-uniform base and a 32-bit lane offset (one address register
-// instead of two).
+// Stores like st16_out (not known to the compiler) with a wave-uniform base and a 32-bit lane
+// offset (one address register instead of two), 16 and 4 bytes.
 // sgpr_base_note: a vector-memory instruction must not read a scalar register within five wait
 // states of a VECTOR instruction that wrote it (v_readlane / v_readfirstlane - which is how the
 // compiler brings back a base address it had to park in a vector register).  The compiler

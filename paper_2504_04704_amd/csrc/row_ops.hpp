@@ -145,17 +145,8 @@ template <int VEC>
 struct TRefFast {
   float iv[VEC], sh[VEC];
   bool wide;
-  __device__ __forceinline__ void from(const TStats<VEC>& s) {
-    float big = 0.f;
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      iv[j] = inv_range(s.mn[j], s.mx[j]);
-      sh[j] = fmaf(-s.mn[j], iv[j], -0.5f);
-      big = fmaxf(big, fabsf(sh[j]));
-    }
-    wide = __any(big > 64.f);
-  }
-  // the same from values computed elsewhere (VEC consecutive channels each)
+  // iv and sh of the lane's VEC consecutive channels, as one thread per channel computed them
+  // (iv = inv_range(mn, mx), sh = fma(-mn, iv, -1/2))
   __device__ __forceinline__ void load(const float* ivp, const float* shp) {
     float big = 0.f;
 #pragma unroll

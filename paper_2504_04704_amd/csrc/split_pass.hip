@@ -1,4 +1,6 @@
-// Tensor-split streaming LagKV kernel for gfx950 (the default one-shot kernel).
+// Tensor-split streaming LagKV kernel for gfx950: the one-shot pass for everything the
+// register-resident kernel does not take (Eq. 16 scoring, lags other than 128, 256 or 512 rows,
+// rows other than 256 bytes), and for any shape on request.
 //
 // A workgroup walks a segment of one stream backwards and scores chunk p with the
 // statistics of chunk p+1 while folding chunk p's own min/max for chunk p-1, so every
@@ -6,9 +8,9 @@
 // the second half only V rows:
 // a lane carries the statistics of ONE tensor, which halves the register footprint and
 // lets 16 wavefronts share a CU (4 per SIMD) with eight 16-byte loads in flight each.
-// The kept rows are re-read for the compaction right after the selection; the chunks
-// in flight (2 workgroups per CU x 2 x L rows) are sized to stay within the 256 MiB
-// memory-side cache, so that re-read does not go to HBM.
+// The kept rows are re-read for the compaction right after the selection (measured: 1.24 to
+// 1.29 times the algorithmic bytes cross the L2; the 256 MiB memory-side cache serves part of
+// that second read of the chunks in flight, 2 workgroups per CU x 2 x L rows).
 #include "lagkv_internal.hpp"
 #include "lds_dma.hpp"
 #include "row_ops.hpp"
