@@ -134,7 +134,7 @@ def timed_steps(step, steps: int, warmup: int):
 
 def copy_rate_gbs(src, dst, n=3):
     """Read+write rate of a plain device copy between two of the workload's own buffers
-    (dst.numel() elements): the yardstick SURVEY-style rooflines call 'copy bandwidth'."""
+    (dst.numel() elements): the yardstick usually called 'copy bandwidth'."""
     import torch
     flat_s, flat_d = src.reshape(-1), dst.reshape(-1)
     cnt = min(flat_s.numel(), flat_d.numel())
