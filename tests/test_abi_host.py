@@ -155,6 +155,11 @@ def test_calls_reject_bad_arguments_before_touching_the_device(lib):
     bad_stride = lagkv.make_params(1, 2, 64, 16, 128, 0.5, lagkv.F32, strides=(0, 0, 32))
     assert lib.lagkv_compress(C.byref(bad_stride), fake, fake, 1024, fake, fake, None, None, None, 0,
                               None) == lagkv.ESHAPE
+    # positions are int32: a cache of 2^31 rows or more is refused before anything is enqueued
+    for T_big in (2 ** 31, 2 ** 40):
+        assert lib.lagkv_compress(C.byref(p), fake, fake, T_big, fake, fake, None, None, None, 0, None) == lagkv.ESHAPE
+        assert lib.lagkv_score(C.byref(p), fake, fake, T_big, fake, None, 0, None) == lagkv.ESHAPE
+        assert lagkv.workspace_bytes(p, T_big) == 0
     # a shape only the three-kernel path serves needs a workspace
     odd = lagkv.make_params(1, 2, 42, 16, 128, 0.5, lagkv.F32)
     need = lagkv.workspace_bytes(odd, 1024)

@@ -634,6 +634,20 @@ def _full_config(name, n_sample, want_scores=True):
     return out, rep
 
 
+@pytest.mark.parametrize("L,r,path", [(512, 0.25, lagkv.PATH_AUTO), (1024, 0.125, lagkv.PATH_AUTO), (128, 0.25, lagkv.PATH_FUSED)])
+def test_a_stream_of_a_million_tokens(L, r, path):
+    """One long context instead of many streams: 2^20 tokens and a ragged end per stream (two streams,
+    so the register-resident kernel cuts each into 128 segments; the streaming kernel likewise), every
+    chunk against the oracle, scores included."""
+    T = 16 + (1 << 20) + 37
+    say("a million tokens", L, r, path)
+    K, V = gen(1, 2, T, 128, torch.bfloat16, seed=2020 + L)
+    out, rep = run_and_check(K, V, 16, L, r, launch=hint(path))
+    pl = O.plan(T, 16, L, r)
+    assert out.plan.T_out == pl["T_out"] and rep.chunks == 2 * pl["n_scored"]
+    say("ok: chunks", rep.chunks, "flipped", rep.flipped_chunks, "max rel", rep.max_score_rel)
+
+
 def test_config2_llama8b_16k():
     out, _ = _full_config("cfg2_llama8b_16k", 256)  # every stream
     assert out.plan.T_out == 4288
