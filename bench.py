@@ -161,6 +161,10 @@ def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None
     from paper_2504_04704_amd import lagkv, placement, synth
 
     cfg = synth.CONFIGS[cfg_name or args.config]
+    if cfg_name is None and (args.lag or args.ratio):
+        # another point of the paper's lag x ratio grid on the same cache (no recorded traffic for it)
+        L, r = args.lag or cfg.L, args.ratio or cfg.r
+        cfg = cfg.scaled(L=L, r=r, name=f"{cfg.name}_L{L}_r{r:g}")
     steps = steps or args.steps
     warmup = args.warmup if warmup is None else warmup
     placements = args.placements if placements is None else placements
@@ -252,7 +256,7 @@ def bench_compress(args, cfg_name=None, steps=None, warmup=None, placements=None
         ids = synth.stream_sample(cfg.streams, cpu_streams or args.cpu_streams)
         res["cpu_baseline"] = cpu_baseline_compress(K, V, cfg, ids, cfg.layers * cfg.H,
                                                     cpu_single or max(1, len(ids) // 4))
-    if with_ablations and args.variant == "lag":
+    if with_ablations and args.variant == "lag" and not (args.lag or args.ratio):
         # the paper's scoring ablations (Eq. 14-15, Eq. 16) on the same resident buffers
         abl = []
         for vname, vid in (("local", lagkv.SCORE_LOCAL), ("l2", lagkv.SCORE_L2)):
@@ -478,6 +482,8 @@ def main():
     ap.add_argument("--workload", choices=["all", "compress", "decode", "copy"], default="all")
     ap.add_argument("--only-headline", action="store_true", help="with --workload all: skip the secondary workloads")
     ap.add_argument("--config", default="cfg4_llama8b_128k_b4")
+    ap.add_argument("--lag", type=int, default=0, help="with --only-headline: L instead of the configuration's")
+    ap.add_argument("--ratio", type=float, default=0.0, help="with --only-headline: r instead of the configuration's")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline legs")
     ap.add_argument("--cpu-streams", type=int, default=96,
                     help="streams the CPU oracle baseline is timed on (about 10-15 s of CPU work)")
